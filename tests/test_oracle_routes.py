@@ -1,0 +1,154 @@
+"""The oracle's three routes agree: full recompute == incremental clean cache == textbook next-token decoder.
+
+These are the checks the problem statement names: the cached block step equals a full-attention recompute
+without a cache at *every* step; block size 1 is greedy next-token decoding (abstract, Sec. 3.3); the result of
+a step is a function of the token history alone (Sec. 3.2: the model "perceives history" and the block).
+"""
+import numpy as np
+import pytest
+
+from helpers import make_model, oracle_model, rel_err, small_cfg
+from oracle import oracle as orc
+from paper_2509_24007_amd import inputs as syn
+
+
+@pytest.fixture(scope="module")
+def model():
+    m = small_cfg()
+    g, layers = make_model(m, seed=11, std=0.3)
+    return m, oracle_model(m, g, layers)
+
+
+@pytest.mark.parametrize("D,tau", [(1, 0.5), (2, 0.3), (4, 0.05), (8, 0.02)])
+def test_cached_equals_brute_every_step(model, D, tau):
+    m, om = model
+    for plen in (1, 2, 3, 5, 17):
+        prompt = syn.uniform_int(plen, f"p{D}", plen, 0, m.vocab - 1).numpy()
+        seq = orc.Seq(om, 128)
+        seq.prefill(prompt)
+        gammas = []
+        for step in range(6):
+            hist = seq.tokens
+            lc, ic, cc, gc = seq.step(D, tau)
+            lb, ib, cb, gb = orc.brute_step(om, hist, D, tau)
+            assert rel_err(lc, lb) < 1e-11
+            np.testing.assert_array_equal(ic, ib)
+            np.testing.assert_allclose(cc, cb, rtol=1e-6)
+            assert gc == gb and 1 <= gc <= D
+            # a repeated step is idempotent (nothing is published before commit)
+            l2, i2, c2, g2 = seq.step(D, tau)
+            np.testing.assert_array_equal(l2, lc)
+            assert seq.commit() == 0
+            assert seq.n == len(hist) + gc and seq.c == len(hist)
+            np.testing.assert_array_equal(seq.tokens[-gc:], ic[:gc])
+            gammas.append(gc)
+        if D >= 4:
+            assert max(gammas) > 1, "thresholds chosen so that multi-token acceptance is exercised"
+
+
+def test_every_prompt_length(model):
+    m, om = model
+    for plen in range(1, 41):
+        prompt = syn.uniform_int(77, f"q{plen}", plen, 0, m.vocab - 1).numpy()
+        seq = orc.Seq(om, 64)
+        seq.prefill(prompt)
+        lc, ic, cc, gc = seq.step(4, 0.1)
+        lb, ib, cb, gb = orc.brute_step(om, prompt, 4, 0.1)
+        assert rel_err(lc, lb) < 1e-11 and gc == gb
+
+
+def test_block_size_one_is_greedy_next_token_decoding(model):
+    m, om = model
+    prompt = syn.uniform_int(5, "ntp", 6, 0, m.vocab - 1).numpy()
+    seq = orc.Seq(om, 64)
+    seq.prefill(prompt)
+    hist = list(prompt)
+    for _ in range(10):
+        z = orc.ntp_logits(om, hist)
+        lc, ic, cc, gc = seq.step(1, 0.99)
+        assert gc == 1
+        assert rel_err(lc[0], z) < 1e-11
+        assert int(ic[0]) == int(np.argmax(z))
+        lb, ib, _, _ = orc.brute_step(om, hist, 1, 0.99)
+        assert rel_err(lb[0], z) < 1e-11
+        seq.commit()
+        hist.append(int(ic[0]))
+    np.testing.assert_array_equal(seq.tokens, hist)
+
+
+def test_first_block_row_is_not_the_causal_row(model):
+    """Row s sees the masks to its right, so for D > 1 its logits differ from next-token logits."""
+    m, om = model
+    prompt = syn.uniform_int(9, "nc", 8, 0, m.vocab - 1).numpy()
+    lb, _, _, _ = orc.brute_step(om, prompt, 4, 0.5)
+    z = orc.ntp_logits(om, prompt)
+    assert rel_err(lb[0], z) > 1e-4
+
+
+def test_step_is_a_function_of_token_history(model):
+    """Different acceptance histories that produce the same tokens give the same next step."""
+    m, om = model
+    D = 4
+    prompt = syn.uniform_int(21, "h", 5, 0, m.vocab - 1).numpy()
+    extra = syn.uniform_int(21, "e", 6, 0, m.vocab - 1).numpy()
+    results = []
+    for split in ([1, 1, 1, 1, 1, 1], [4, 2], [2, 4], [3, 3]):
+        seq = orc.Seq(om, 64)
+        seq.prefill(prompt)
+        o = 0
+        for cnt in split:
+            seq.step(D, 0.5)
+            assert seq.commit(extra[o:o + cnt], cnt) == 0
+            o += cnt
+        np.testing.assert_array_equal(seq.tokens, np.concatenate([prompt, extra]))
+        results.append(seq.step(D, 0.5)[0])
+    for r in results[1:]:
+        assert rel_err(r, results[0]) < 1e-11
+    # and equals prefill of the whole history at once
+    seq = orc.Seq(om, 64)
+    seq.prefill(np.concatenate([prompt, extra]))
+    assert rel_err(seq.step(D, 0.5)[0], results[0]) < 1e-11
+
+
+def test_cache_holds_causal_kv_of_real_tokens(model):
+    """After commits the cache equals the K/V a plain causal prefill of the same tokens produces."""
+    m, om = model
+    prompt = syn.uniform_int(31, "c", 4, 0, m.vocab - 1).numpy()
+    a = orc.Seq(om, 64)
+    a.prefill(prompt)
+    for _ in range(4):
+        a.step(4, 0.05)
+        a.commit()
+    a.step(4, 0.05)                  # flush: pending K/V are written by the next step
+    a.commit()
+    b = orc.Seq(om, 64)
+    b.prefill(a.tokens[:a.c])
+    for layer in range(m.n_layers):
+        for pos in range(a.c):
+            for hk in range(m.n_kv_heads):
+                ka, va = a.read_kv(layer, pos, hk)
+                kb, vb = b.read_kv(layer, pos, hk)
+                assert rel_err(ka, kb) < 1e-11 and rel_err(va, vb) < 1e-11
+
+
+def test_commit_rules(model):
+    m, om = model
+    seq = orc.Seq(om, 32)
+    seq.prefill([1, 2, 3])
+    assert seq.commit() == -3                      # no step to commit
+    seq.step(4, 0.5)
+    assert seq.commit([5, 6, 7, 8, 9], 5) == -1    # count > D
+    assert seq.commit([5], 0) == -1                # count < 1
+    assert seq.commit([5, 6], 2) == 0
+    assert seq.commit() == -3                      # already committed
+
+
+def test_entropy_rule_runs_through_step(model):
+    m, om = model
+    seq = orc.Seq(om, 32)
+    seq.prefill([4, 8, 15, 16])
+    l, ids, conf, g = seq.step(4, 0.01, conf_fn=1)
+    for k in range(4):
+        assert abs(conf[k] - np.float32(orc.conf_entropy(l[k]))) < 1e-7
+        assert 0.0 <= conf[k] <= 1.0
+    assert g == orc.gamma(conf, 0.01)
