@@ -1,0 +1,107 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "sdlm.h"
+
+namespace sdlm {
+
+constexpr int PAGE = 16;        // tokens per K/V tile (page)
+constexpr int GROUP_ROWS = 16;  // most rows of one sequence handled together by one attention work item
+constexpr int MAX_D = 16;
+
+typedef uint16_t bf16_t;        // bf16 bit pattern
+
+__host__ __device__ inline float bf16_to_f(bf16_t v)
+{
+    union { uint32_t u; float f; } c;
+    c.u = (uint32_t)v << 16;
+    return c.f;
+}
+__host__ __device__ inline bf16_t f_to_bf16(float f)   // round to nearest even
+{
+    union { uint32_t u; float f; } c;
+    c.f = f;
+    if ((c.u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((c.u >> 16) | 0x40);   // NaN stays NaN
+    c.u += 0x7fffu + ((c.u >> 16) & 1u);
+    return (bf16_t)(c.u >> 16);
+}
+
+template <typename T> __device__ inline float to_f(T v);
+template <> __device__ inline float to_f<float>(float v) { return v; }
+template <> __device__ inline float to_f<bf16_t>(bf16_t v) { return bf16_to_f(v); }
+template <typename T> __device__ inline T from_f(float v);
+template <> __device__ inline float from_f<float>(float v) { return v; }
+template <> __device__ inline bf16_t from_f<bf16_t>(float v) { return f_to_bf16(v); }
+
+// ---- K/V tile layout -------------------------------------------------------------------------------------
+// The cache is a pool of tiles.  One tile holds 16 consecutive positions of one (layer, kv head): first a K
+// block then a V block of 16*d elements each.  Inside the blocks the elements are ordered the way the
+// matrix-core attention kernel consumes them, so that a wavefront's operand load is one contiguous run:
+//   K block: [d/8][16 slots][8]        element (slot, i) at (i/8)*128 + slot*8 + i%8
+//   V block: [d/16][4][16][4 slots]    element (slot, i) at ((i/16)*4 + slot/4)*64 + (i%16)*4 + slot%4
+// Pool order: [layer][tile][kv head][K block | V block].  Tiles n_pages .. n_pages+max_batch-1 of every layer
+// are the per-sequence staging tiles that hold the D block rows' K/V during a step.
+__host__ __device__ inline int k_off(int slot, int i) { return (i >> 3) * (PAGE * 8) + slot * 8 + (i & 7); }
+__host__ __device__ inline int v_off(int slot, int i) { return (((i >> 4) << 2) + (slot >> 2)) * 64 + ((i & 15) << 2) + (slot & 3); }
+
+// Packed description of the rows of one forward pass (device arrays).
+struct RowMeta {
+    int32_t *tok, *pos, *seq, *kind, *lim;  // [max_rows]; kind: -1 pending, else block index; lim: visible cache keys
+    int32_t *grp_row0, *grp_n, *grp_seq;    // [max_groups]: runs of <= GROUP_ROWS rows of one sequence
+    int32_t *blk_row;                       // [max_batch*D]: packed row index of block row (b, j)
+    int32_t *counts;                        // [4]: rows R, groups, block rows, unused
+};
+
+// Per-sequence state (device arrays).
+struct SeqState {
+    int32_t *n, *c, *last_tok;      // [B]
+    int32_t *pend_tok;              // [B][D]: tokens at positions c..n-1
+    int32_t *page_table;            // [B][pages_per_seq]
+    int32_t *pages_backed;          // [B]
+    int32_t *alloc;                 // [0] next free page, [1] error bits (1: pool exhausted, 2: count clamped)
+    int32_t *last_ids, *last_count; // [B][D], [B]: the last step's result
+};
+
+struct KvGeom {
+    int32_t n_kv_heads, head_dim, pages_per_seq, staging_base;  // staging tile of sequence b = staging_base + b
+    size_t layer_stride;                                         // elements per layer of the pool
+    __host__ __device__ size_t tile(int page, int kvh) const { return ((size_t)page * n_kv_heads + kvh) * (size_t)(2 * PAGE * head_dim); }
+};
+
+// ---- kernel launchers (generic kernels: any supported shape, fp32 or bf16 storage, fp32 arithmetic) ----------
+enum GemmEpi { EPI_STORE_F32 = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LOGITS = 3 };
+
+struct GemmArgs {
+    const void *X;      // [R, K] elem
+    const void *W;      // [N, K] elem
+    const void *W2;     // second matrix for EPI_SWIGLU (up projection)
+    const void *bias;   // [N] elem or null
+    float *Yf;          // fp32 destination (STORE_F32 / RESID / LOGITS)
+    void *Yt;           // elem destination (SWIGLU)
+    const int32_t *pR;  // device row count
+    int max_rows, N, K;
+    float scale;
+};
+
+void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id);
+void launch_embed(hipStream_t s, int dtype, float *x, const void *E, const RowMeta &rm, int max_rows, int h);
+void launch_rmsnorm(hipStream_t s, int dtype, void *out, const float *x, const void *g, int h, float eps,
+                    const int32_t *row_index, const int32_t *p_count, int max_rows);
+void launch_gemm_generic(hipStream_t s, int dtype, int epi, const GemmArgs &a);
+void launch_rope_scatter(hipStream_t s, int dtype, const float *qkv, void *q_out, void *pool_layer, const KvGeom &kg,
+                         const RowMeta &rm, const SeqState &st, const float2 *rope, int n_q_heads, int max_rows);
+void launch_attn_generic(hipStream_t s, int dtype, const void *q, void *out, const void *pool_layer, const KvGeom &kg,
+                         const RowMeta &rm, const SeqState &st, int n_q_heads, int D, int max_rows);
+void launch_lm_reduce(hipStream_t s, const float *logits, int V, int32_t *ids, float *conf, int conf_fn,
+                      const int32_t *p_rows, int max_rows);
+void launch_accept(hipStream_t s, const SeqState &st, const int32_t *ids_rows, const float *conf_rows, int B, int D,
+                   float tau, int rule, int32_t *ids_out, int32_t *count_out, float *conf_out);
+void launch_commit(hipStream_t s, const SeqState &st, int B, int D, const int32_t *ids_ovr, const int32_t *cnt_ovr,
+                   int paged, int n_pages, int pages_per_seq);
+void launch_read_kv(hipStream_t s, int dtype, const void *pool_layer, const KvGeom &kg, const SeqState &st, int seq,
+                    int kvh, int pos0, int count, float *k_out, float *v_out);
+
+}  // namespace sdlm

@@ -1,0 +1,435 @@
+// Shape-generic kernels of the block-decode step: row assembly, embedding gather, RMSNorm, a tiled FMA GEMM with
+// fused epilogues, RoPE + K/V placement, block-masked attention, the vocabulary reduction, prefix acceptance
+// and commit.  Storage is fp32 or bf16; all arithmetic is fp32.  They serve the fp32 debug mode and every small
+// integer/elementwise step of the bf16 mode; the bf16 mode's contractions run on the matrix-core kernels.
+#include "internal.hpp"
+
+namespace sdlm {
+
+// ------------------------------------------------------------------------------------------------ row assembly
+// Rows of a decode step, per sequence: the pending tokens (positions c..n-1, causal), then the block
+// [x_last, [m] x (D-1)] at positions n-1 .. n+D-2 (block definition, Sec. 3.2).  A block row may see the cache
+// below position s = n-1 only; the causal copy of x_last at s is for later steps.
+__global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mask_id)
+{
+    __shared__ int row0[1025], grp0[1025];
+    if (threadIdx.x == 0) {
+        int r = 0, g = 0;
+        for (int b = 0; b < B; ++b) {
+            row0[b] = r; grp0[b] = g;
+            int rows = st.n[b] - st.c[b] + D;
+            r += rows;
+            g += (rows + GROUP_ROWS - 1) / GROUP_ROWS;
+        }
+        row0[B] = r; grp0[B] = g;
+        rm.counts[0] = r; rm.counts[1] = g; rm.counts[2] = B * D; rm.counts[3] = 0;
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+        int n = st.n[b], c = st.c[b], p = n - c, r = row0[b];
+        for (int i = 0; i < p; ++i, ++r) {
+            rm.tok[r] = st.pend_tok[b * D + i];
+            rm.pos[r] = c + i; rm.seq[r] = b; rm.kind[r] = -1; rm.lim[r] = c + i + 1;
+        }
+        for (int j = 0; j < D; ++j, ++r) {
+            rm.tok[r] = j == 0 ? st.last_tok[b] : mask_id;
+            rm.pos[r] = n - 1 + j; rm.seq[r] = b; rm.kind[r] = j; rm.lim[r] = n - 1;
+            rm.blk_row[b * D + j] = r;
+        }
+        int rows = p + D, g = grp0[b];
+        for (int o = 0; o < rows; o += GROUP_ROWS, ++g) {
+            rm.grp_row0[g] = row0[b] + o;
+            rm.grp_n[g] = min(GROUP_ROWS, rows - o);
+            rm.grp_seq[g] = b;
+        }
+    }
+}
+
+void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id)
+{
+    hipLaunchKernelGGL(assemble_decode_k, dim3(1), dim3(256), 0, s, st, rm, B, D, mask_id);
+}
+
+// ------------------------------------------------------------------------------------------------ embedding
+template <typename T>
+__global__ void embed_k(float *x, const T *E, const int32_t *tok, const int32_t *pR, int h)
+{
+    int r = blockIdx.x;
+    if (r >= *pR) return;
+    const T *e = E + (size_t)tok[r] * h;
+    for (int k = threadIdx.x; k < h; k += blockDim.x) x[(size_t)r * h + k] = to_f<T>(e[k]);
+}
+
+void launch_embed(hipStream_t s, int dtype, float *x, const void *E, const RowMeta &rm, int max_rows, int h)
+{
+    if (dtype == 0) hipLaunchKernelGGL(embed_k<float>, dim3(max_rows), dim3(256), 0, s, x, (const float *)E, rm.tok, rm.counts, h);
+    else hipLaunchKernelGGL(embed_k<bf16_t>, dim3(max_rows), dim3(256), 0, s, x, (const bf16_t *)E, rm.tok, rm.counts, h);
+}
+
+// ------------------------------------------------------------------------------------------------ RMSNorm
+__device__ inline float block_sum(float v, float *red)
+{
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[w] = v;
+    __syncthreads();
+    float t = 0.f;
+    for (int i = 0; i < nw; ++i) t += red[i];
+    return t;
+}
+
+// out[j,:] = x[row,:] * g / sqrt(mean(x[row,:]^2) + eps), row = row_index ? row_index[j] : j
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_k(T *out, const float *x, const T *g, int h, float eps,
+                                                 const int32_t *row_index, const int32_t *p_count)
+{
+    __shared__ float red[4];
+    int j = blockIdx.x;
+    if (j >= *p_count) return;
+    const float *xr = x + (size_t)(row_index ? row_index[j] : j) * h;
+    float ss = 0.f;
+    for (int k = threadIdx.x; k < h; k += 256) ss += xr[k] * xr[k];
+    ss = block_sum(ss, red);
+    float inv = 1.0f / sqrtf(ss / (float)h + eps);
+    for (int k = threadIdx.x; k < h; k += 256) out[(size_t)j * h + k] = from_f<T>(xr[k] * inv * to_f<T>(g[k]));
+}
+
+void launch_rmsnorm(hipStream_t s, int dtype, void *out, const float *x, const void *g, int h, float eps,
+                    const int32_t *row_index, const int32_t *p_count, int max_rows)
+{
+    if (dtype == 0) hipLaunchKernelGGL(rmsnorm_k<float>, dim3(max_rows), dim3(256), 0, s, (float *)out, x, (const float *)g, h, eps, row_index, p_count);
+    else hipLaunchKernelGGL(rmsnorm_k<bf16_t>, dim3(max_rows), dim3(256), 0, s, (bf16_t *)out, x, (const bf16_t *)g, h, eps, row_index, p_count);
+}
+
+// ------------------------------------------------------------------------------------------------ GEMM (FMA)
+// Y[r, n] = sum_k X[r, k] * W[n, k]; 64x64 tile, 16-deep slices through LDS, 4x4 outputs per thread.
+__device__ inline float silu_f(float v) { return v / (1.0f + __expf(-v)); }
+
+template <typename T, int EPI>
+__global__ __launch_bounds__(256) void gemm_generic_k(GemmArgs a)
+{
+    const int R = min(*a.pR, a.max_rows);
+    const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+    if (m0 >= R) return;
+    constexpr bool DUAL = EPI == EPI_SWIGLU;
+    __shared__ float Xs[16][65], Ws[16][65], Us[DUAL ? 16 : 1][65];
+    const T *X = (const T *)a.X, *W = (const T *)a.W, *W2 = (const T *)a.W2;
+    const int t = threadIdx.x, tx = t & 15, ty = t >> 4, K = a.K, N = a.N;
+    float acc[4][4] = {}, acc2[4][4] = {};
+    for (int k0 = 0; k0 < K; k0 += 16) {
+        for (int e = t; e < 1024; e += 256) {
+            int row = e >> 4, kk = e & 15;
+            bool kin = k0 + kk < K;
+            Xs[kk][row] = (kin && m0 + row < R) ? to_f<T>(X[(size_t)(m0 + row) * K + k0 + kk]) : 0.f;
+            bool nin = kin && n0 + row < N;
+            Ws[kk][row] = nin ? to_f<T>(W[(size_t)(n0 + row) * K + k0 + kk]) : 0.f;
+            if (DUAL) Us[kk][row] = nin ? to_f<T>(W2[(size_t)(n0 + row) * K + k0 + kk]) : 0.f;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            float xv[4], wv[4], uv[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { xv[i] = Xs[kk][ty * 4 + i]; wv[i] = Ws[kk][tx * 4 + i]; uv[i] = DUAL ? Us[kk][tx * 4 + i] : 0.f; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    acc[i][j] += xv[i] * wv[j];
+                    if (DUAL) acc2[i][j] += xv[i] * uv[j];
+                }
+        }
+        __syncthreads();
+    }
+    for (int i = 0; i < 4; ++i) {
+        int r = m0 + ty * 4 + i;
+        if (r >= R) continue;
+        for (int j = 0; j < 4; ++j) {
+            int n = n0 + tx * 4 + j;
+            if (n >= N) continue;
+            size_t o = (size_t)r * N + n;
+            if (EPI == EPI_STORE_F32) a.Yf[o] = acc[i][j] + (a.bias ? to_f<T>(((const T *)a.bias)[n]) : 0.f);
+            else if (EPI == EPI_RESID) a.Yf[o] += acc[i][j];
+            else if (EPI == EPI_SWIGLU) ((T *)a.Yt)[o] = from_f<T>(silu_f(acc[i][j]) * acc2[i][j]);
+            else a.Yf[o] = acc[i][j] * a.scale;
+        }
+    }
+}
+
+template <typename T>
+static void gemm_generic_t(hipStream_t s, int epi, const GemmArgs &a)
+{
+    dim3 grid((a.N + 63) / 64, (a.max_rows + 63) / 64), block(256);
+    switch (epi) {
+    case EPI_STORE_F32: hipLaunchKernelGGL((gemm_generic_k<T, EPI_STORE_F32>), grid, block, 0, s, a); break;
+    case EPI_RESID: hipLaunchKernelGGL((gemm_generic_k<T, EPI_RESID>), grid, block, 0, s, a); break;
+    case EPI_SWIGLU: hipLaunchKernelGGL((gemm_generic_k<T, EPI_SWIGLU>), grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL((gemm_generic_k<T, EPI_LOGITS>), grid, block, 0, s, a); break;
+    }
+}
+
+void launch_gemm_generic(hipStream_t s, int dtype, int epi, const GemmArgs &a)
+{
+    if (dtype == 0) gemm_generic_t<float>(s, epi, a);
+    else gemm_generic_t<bf16_t>(s, epi, a);
+}
+
+// ------------------------------------------------------------------------------------------------ RoPE + K/V placement
+// qkv: raw projections [R, (Hq + 2 Hkv) d] fp32.  Queries and keys are rotated at the row's position (rotate-half
+// pairing i <-> i + d/2).  A pending row's K/V go to the cache slot of its position: they are final.  A block
+// row's K/V go to its sequence's staging tile, slot = block index: they are never cached.
+template <typename T>
+__global__ __launch_bounds__(256) void rope_scatter_k(const float *qkv, T *q_out, T *pool, KvGeom kg, RowMeta rm, SeqState st,
+                                                      const float2 *rope, int Hq)
+{
+    int r = blockIdx.x;
+    if (r >= rm.counts[0]) return;
+    const int d = kg.head_dim, half = d >> 1, Hk = kg.n_kv_heads, nq = Hq * d, nk = Hk * d;
+    const float *row = qkv + (size_t)r * (nq + 2 * nk);
+    const int pos = rm.pos[r], kind = rm.kind[r], b = rm.seq[r];
+    const float2 *cs = rope + (size_t)pos * half;
+    int page, slot;
+    if (kind < 0) { page = st.page_table[(size_t)b * kg.pages_per_seq + pos / PAGE]; slot = pos % PAGE; }
+    else { page = kg.staging_base + b; slot = kind; }
+    for (int e = threadIdx.x; e < Hq * half; e += 256) {
+        int hq = e / half, i = e % half;
+        float2 t = cs[i];
+        float x0 = row[hq * d + i], x1 = row[hq * d + i + half];
+        q_out[(size_t)r * nq + hq * d + i] = from_f<T>(x0 * t.x - x1 * t.y);
+        q_out[(size_t)r * nq + hq * d + i + half] = from_f<T>(x1 * t.x + x0 * t.y);
+    }
+    if (page < 0) return;   // unbacked position: only reachable after a reported pool exhaustion
+    for (int e = threadIdx.x; e < Hk * half; e += 256) {
+        int hk = e / half, i = e % half;
+        float2 t = cs[i];
+        const float *kr = row + nq + hk * d, *vr = row + nq + nk + hk * d;
+        T *tile = pool + kg.tile(page, hk);
+        T *Kb = tile, *Vb = tile + PAGE * d;
+        float x0 = kr[i], x1 = kr[i + half];
+        Kb[k_off(slot, i)] = from_f<T>(x0 * t.x - x1 * t.y);
+        Kb[k_off(slot, i + half)] = from_f<T>(x1 * t.x + x0 * t.y);
+        Vb[v_off(slot, i)] = from_f<T>(vr[i]);
+        Vb[v_off(slot, i + half)] = from_f<T>(vr[i + half]);
+    }
+}
+
+void launch_rope_scatter(hipStream_t s, int dtype, const float *qkv, void *q_out, void *pool_layer, const KvGeom &kg,
+                         const RowMeta &rm, const SeqState &st, const float2 *rope, int n_q_heads, int max_rows)
+{
+    if (dtype == 0) hipLaunchKernelGGL(rope_scatter_k<float>, dim3(max_rows), dim3(256), 0, s, qkv, (float *)q_out, (float *)pool_layer, kg, rm, st, rope, n_q_heads);
+    else hipLaunchKernelGGL(rope_scatter_k<bf16_t>, dim3(max_rows), dim3(256), 0, s, qkv, (bf16_t *)q_out, (bf16_t *)pool_layer, kg, rm, st, rope, n_q_heads);
+}
+
+// ------------------------------------------------------------------------------------------------ attention
+// One wavefront per (row, query head).  Keys: the cache positions [0, lim) of the row's sequence and, for a
+// block row, the D staging keys of the block (mask equation, Sec. 3.3: causal below the block start, full
+// mutual attention inside the block).  Each lane walks a strided subset of the keys with a running
+// (max, sum, output); the 64 partial results are merged at the end.
+template <typename T, int HD>
+__global__ __launch_bounds__(64) void attn_generic_k(const T *q, T *out, const T *pool, KvGeom kg, RowMeta rm, SeqState st,
+                                                     int Hq, int D)
+{
+    const int r = blockIdx.y;
+    if (r >= rm.counts[0]) return;
+    const int hq = blockIdx.x, G = Hq / kg.n_kv_heads, hk = hq / G, lane = threadIdx.x;
+    const int b = rm.seq[r], lim = rm.lim[r], kind = rm.kind[r];
+    const int total = lim + (kind >= 0 ? D : 0);
+    __shared__ float qs[HD];
+    __shared__ float part[64][HD + 1];
+    const float scale = 1.0f / sqrtf((float)HD);
+    for (int i = lane; i < HD; i += 64) qs[i] = to_f<T>(q[((size_t)r * Hq + hq) * HD + i]);
+    __syncthreads();
+    float m = -INFINITY, l = 0.f, o[HD];
+#pragma unroll
+    for (int i = 0; i < HD; ++i) o[i] = 0.f;
+    for (int j = lane; j < total; j += 64) {
+        int page, slot;
+        if (j < lim) { page = st.page_table[(size_t)b * kg.pages_per_seq + j / PAGE]; slot = j % PAGE; }
+        else { page = kg.staging_base + b; slot = j - lim; }
+        const T *Kb = pool + kg.tile(page, hk), *Vb = Kb + PAGE * HD;
+        float sdot = 0.f;
+#pragma unroll
+        for (int i = 0; i < HD; ++i) sdot += qs[i] * to_f<T>(Kb[k_off(slot, i)]);
+        sdot *= scale;
+        float mn = fmaxf(m, sdot), corr = __expf(m - mn), p = __expf(sdot - mn);
+        l = l * corr + p;
+#pragma unroll
+        for (int i = 0; i < HD; ++i) o[i] = o[i] * corr + p * to_f<T>(Vb[v_off(slot, i)]);
+        m = mn;
+    }
+    float M = m;
+    for (int s = 32; s > 0; s >>= 1) M = fmaxf(M, __shfl_xor(M, s));
+    float f = (m == -INFINITY) ? 0.f : __expf(m - M);
+    float L = l * f;
+    for (int s = 32; s > 0; s >>= 1) L += __shfl_xor(L, s);
+#pragma unroll
+    for (int i = 0; i < HD; ++i) part[lane][i] = o[i] * f;
+    __syncthreads();
+    for (int i = lane; i < HD; i += 64) {
+        float acc = 0.f;
+        for (int w = 0; w < 64; ++w) acc += part[w][i];
+        out[((size_t)r * Hq + hq) * HD + i] = from_f<T>(acc / L);
+    }
+}
+
+template <typename T>
+static void attn_generic_t(hipStream_t s, const void *q, void *out, const void *pool_layer, const KvGeom &kg,
+                           const RowMeta &rm, const SeqState &st, int Hq, int D, int max_rows)
+{
+    dim3 grid(Hq, max_rows), block(64);
+    switch (kg.head_dim) {
+    case 32: hipLaunchKernelGGL((attn_generic_k<T, 32>), grid, block, 0, s, (const T *)q, (T *)out, (const T *)pool_layer, kg, rm, st, Hq, D); break;
+    case 64: hipLaunchKernelGGL((attn_generic_k<T, 64>), grid, block, 0, s, (const T *)q, (T *)out, (const T *)pool_layer, kg, rm, st, Hq, D); break;
+    case 96: hipLaunchKernelGGL((attn_generic_k<T, 96>), grid, block, 0, s, (const T *)q, (T *)out, (const T *)pool_layer, kg, rm, st, Hq, D); break;
+    default: hipLaunchKernelGGL((attn_generic_k<T, 128>), grid, block, 0, s, (const T *)q, (T *)out, (const T *)pool_layer, kg, rm, st, Hq, D); break;
+    }
+}
+
+void launch_attn_generic(hipStream_t s, int dtype, const void *q, void *out, const void *pool_layer, const KvGeom &kg,
+                         const RowMeta &rm, const SeqState &st, int n_q_heads, int D, int max_rows)
+{
+    if (dtype == 0) attn_generic_t<float>(s, q, out, pool_layer, kg, rm, st, n_q_heads, D, max_rows);
+    else attn_generic_t<bf16_t>(s, q, out, pool_layer, kg, rm, st, n_q_heads, D, max_rows);
+}
+
+// ------------------------------------------------------------------------------------------------ vocabulary reduction
+// Per block row: arg-max (lowest index on ties), and the confidence of Sec. 3.4: (1) softmax probability of the
+// arg-max token = 1 / sum exp(z - max); (2) 1 - H / log|V| with H = log S - (sum e^{z-m} (z-m)) / S.
+__global__ __launch_bounds__(256) void lm_reduce_k(const float *logits, int V, int32_t *ids, float *conf, int conf_fn,
+                                                   const int32_t *p_rows)
+{
+    int row = blockIdx.x;
+    if (row >= *p_rows) return;
+    const float *z = logits + (size_t)row * V;
+    __shared__ float sm[4];
+    __shared__ int si[4];
+    __shared__ float red[4];
+    float m = -INFINITY;
+    int arg = 0x7fffffff;
+    for (int v = threadIdx.x; v < V; v += 256) {
+        float t = z[v];
+        if (t > m) { m = t; arg = v; }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        float om = __shfl_xor(m, o);
+        int oa = __shfl_xor(arg, o);
+        if (om > m || (om == m && oa < arg)) { m = om; arg = oa; }
+    }
+    if ((threadIdx.x & 63) == 0) { sm[threadIdx.x >> 6] = m; si[threadIdx.x >> 6] = arg; }
+    __syncthreads();
+    m = sm[0]; arg = si[0];
+    for (int w = 1; w < 4; ++w)
+        if (sm[w] > m || (sm[w] == m && si[w] < arg)) { m = sm[w]; arg = si[w]; }
+    float S = 0.f, E = 0.f;
+    for (int v = threadIdx.x; v < V; v += 256) {
+        float dlt = z[v] - m, e = __expf(dlt);
+        S += e;
+        E += e * dlt;
+    }
+    S = block_sum(S, red);
+    E = block_sum(E, red);
+    if (threadIdx.x == 0) {
+        ids[row] = arg;
+        conf[row] = conf_fn == 0 ? 1.0f / S : 1.0f - (logf(S) - E / S) / logf((float)V);
+    }
+}
+
+void launch_lm_reduce(hipStream_t s, const float *logits, int V, int32_t *ids, float *conf, int conf_fn,
+                      const int32_t *p_rows, int max_rows)
+{
+    hipLaunchKernelGGL(lm_reduce_k, dim3(max_rows), dim3(256), 0, s, logits, V, ids, conf, conf_fn, p_rows);
+}
+
+// ------------------------------------------------------------------------------------------------ acceptance
+// gamma_tau (Sec. 3.4): the largest j in 1..D whose cumulative product of confidences is >= tau, at least 1.
+// The product is a float product taken left to right.  rule 1: leading positions whose own confidence is >= tau.
+__global__ void accept_k(SeqState st, const int32_t *ids_rows, const float *conf_rows, int B, int D, float tau, int rule,
+                         int32_t *ids_out, int32_t *count_out, float *conf_out)
+{
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int best = 1;
+    if (rule == 0) {
+        float prod = 1.0f;
+        for (int j = 1; j <= D; ++j) {
+            prod = prod * conf_rows[b * D + j - 1];
+            if (prod >= tau && j > best) best = j;
+        }
+    } else {
+        int j = 0;
+        while (j < D && conf_rows[b * D + j] >= tau) ++j;
+        if (j > best) best = j;
+    }
+    st.last_count[b] = best;
+    count_out[b] = best;
+    for (int j = 0; j < D; ++j) {
+        int id = ids_rows[b * D + j];
+        st.last_ids[b * D + j] = id;
+        ids_out[b * D + j] = id;
+        if (conf_out) conf_out[b * D + j] = conf_rows[b * D + j];
+    }
+}
+
+void launch_accept(hipStream_t s, const SeqState &st, const int32_t *ids_rows, const float *conf_rows, int B, int D,
+                   float tau, int rule, int32_t *ids_out, int32_t *count_out, float *conf_out)
+{
+    hipLaunchKernelGGL(accept_k, dim3((B + 63) / 64), dim3(64), 0, s, st, ids_rows, conf_rows, B, D, tau, rule, ids_out, count_out, conf_out);
+}
+
+// ------------------------------------------------------------------------------------------------ commit
+// c <- n (the pending K/V, already in place, become cache); the accepted tokens become the pending tokens;
+// n <- n + count; the page table grows so that every position < n is backed.
+__global__ void commit_k(SeqState st, int B, int D, const int32_t *ids_ovr, const int32_t *cnt_ovr, int paged, int n_pages,
+                         int pages_per_seq)
+{
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const int32_t *ids = ids_ovr ? ids_ovr + b * D : st.last_ids + b * D;
+    int cnt = cnt_ovr ? cnt_ovr[b] : st.last_count[b];
+    if (cnt < 1 || cnt > D) { atomicOr(&st.alloc[1], 2); cnt = cnt < 1 ? 1 : D; }
+    int n = st.n[b], n_new = n + cnt;
+    int need = (n_new + PAGE - 1) / PAGE - st.pages_backed[b];
+    if (need > 0) {
+        if (!paged || st.pages_backed[b] + need > pages_per_seq) { atomicOr(&st.alloc[1], 1); return; }
+        int first = atomicAdd(&st.alloc[0], need);
+        if (first + need > n_pages) { atomicOr(&st.alloc[1], 1); return; }
+        for (int i = 0; i < need; ++i) st.page_table[(size_t)b * pages_per_seq + st.pages_backed[b] + i] = first + i;
+        st.pages_backed[b] += need;
+    }
+    for (int i = 0; i < cnt; ++i) st.pend_tok[b * D + i] = ids[i];
+    st.last_tok[b] = ids[cnt - 1];
+    st.c[b] = n;
+    st.n[b] = n_new;
+}
+
+void launch_commit(hipStream_t s, const SeqState &st, int B, int D, const int32_t *ids_ovr, const int32_t *cnt_ovr,
+                   int paged, int n_pages, int pages_per_seq)
+{
+    hipLaunchKernelGGL(commit_k, dim3((B + 63) / 64), dim3(64), 0, s, st, B, D, ids_ovr, cnt_ovr, paged, n_pages, pages_per_seq);
+}
+
+// ------------------------------------------------------------------------------------------------ debug read-back
+template <typename T>
+__global__ void read_kv_k(const T *pool, KvGeom kg, SeqState st, int seq, int kvh, int pos0, int count, float *k_out, float *v_out)
+{
+    int d = kg.head_dim;
+    for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < count * d; e += gridDim.x * blockDim.x) {
+        int pos = pos0 + e / d, i = e % d;
+        int page = st.page_table[(size_t)seq * kg.pages_per_seq + pos / PAGE], slot = pos % PAGE;
+        const T *Kb = pool + kg.tile(page, kvh), *Vb = Kb + PAGE * d;
+        k_out[e] = to_f<T>(Kb[k_off(slot, i)]);
+        v_out[e] = to_f<T>(Vb[v_off(slot, i)]);
+    }
+}
+
+void launch_read_kv(hipStream_t s, int dtype, const void *pool_layer, const KvGeom &kg, const SeqState &st, int seq,
+                    int kvh, int pos0, int count, float *k_out, float *v_out)
+{
+    int blocks = (count * kg.head_dim + 255) / 256;
+    if (blocks > 1024) blocks = 1024;
+    if (dtype == 0) hipLaunchKernelGGL(read_kv_k<float>, dim3(blocks), dim3(256), 0, s, (const float *)pool_layer, kg, st, seq, kvh, pos0, count, k_out, v_out);
+    else hipLaunchKernelGGL(read_kv_k<bf16_t>, dim3(blocks), dim3(256), 0, s, (const bf16_t *)pool_layer, kg, st, seq, kvh, pos0, count, k_out, v_out);
+}
+
+}  // namespace sdlm

@@ -1,0 +1,26 @@
+// Matrix-core (MFMA) kernels of the bf16 mode: declarations.
+#pragma once
+#include "internal.hpp"
+
+namespace sdlm {
+
+// True when the bf16 matrix-core path serves this model (bf16, head_dim 128, sizes multiples of the tile steps).
+bool mfma_supported(const sdlm_model_cfg *m);
+// Rows of a packed weight matrix are padded to a multiple of the 32-row tile.
+size_t mfma_pad_n(size_t N);
+// Elements a packed [N, K] matrix occupies (N * K when `packed` is false).
+size_t mfma_packed_elems(bool packed, size_t N, size_t K);
+// Bytes of scratch the split-KV attention and the LM-head partials need.
+size_t mfma_attn_scratch_bytes(const sdlm_model_cfg *m, const sdlm_run_cfg *r, int max_rows);
+
+// Repack rows of a row-major [N, K] bf16 matrix into tile order at row offset dst_row0 of a packed matrix with
+// dst_rows rows.  interleave: 0 plain; 1 / 2: the matrix is the gate / up half of the fused gate-up matrix,
+// whose 32-row tiles alternate gate, up.
+void launch_pack_mfma(hipStream_t s, void *dst, const void *src, int N, int K, int dst_row0, int dst_rows, int interleave);
+void launch_gemm_mfma(hipStream_t s, int epi, const GemmArgs &a);
+void launch_attn_mfma(hipStream_t s, const void *q, void *out, const void *pool_layer, const KvGeom &kg, const RowMeta &rm,
+                      const SeqState &st, int n_q_heads, int D, int max_rows, void *scratch);
+void launch_lmhead_mfma(hipStream_t s, const void *xhat, const void *w_packed, int max_rows, int V, int h, float scale,
+                        int conf_fn, float *logits_out, void *scratch, int32_t *ids, float *conf);
+
+}  // namespace sdlm

@@ -1,0 +1,112 @@
+"""Plumbing shared by the GPU parity tests: build the same synthetic model for the oracle and for the HIP
+library, and drive both in lockstep.  Nothing here computes any part of the method."""
+import numpy as np
+import torch
+
+from helpers import make_model, oracle_model
+from oracle import oracle as orc
+from paper_2509_24007_amd import inputs as syn
+from paper_2509_24007_amd import sdlm
+
+
+def gpu_context(mcfg, g_dev, layers_dev, *, max_batch, max_seq_len, D, tau, paged=False, n_pages=0, conf_fn=0,
+                accept_rule=0, prefill_rows=0):
+    ctx = sdlm.Context(sdlm.model_cfg(mcfg), max_batch=max_batch, max_seq_len=max_seq_len, block_D=D, tau=tau,
+                       paged=paged, n_pages=n_pages, conf_fn=conf_fn, accept_rule=accept_rule, prefill_rows=prefill_rows)
+    ctx.init_weights(g_dev, {l: layers_dev[l] for l in range(mcfg.n_layers)})
+    torch.cuda.synchronize()
+    return ctx
+
+
+def both_models(mcfg, seed, std):
+    """Weights generated once on the CPU (for the oracle) and moved to the GPU unchanged."""
+    g, layers = make_model(mcfg, seed=seed, std=std)
+    om = oracle_model(mcfg, g, layers)
+    g_dev = {k: v.cuda() for k, v in g.items()}
+    layers_dev = [{k: (v.cuda() if v is not None else None) for k, v in L.items()} for L in layers]
+    return om, g_dev, layers_dev
+
+
+class Stats:
+    def __init__(self):
+        self.rows = self.id_near_tie = self.gamma_near_tie = 0
+        self.max_logit_err = self.max_conf_err = 0.0
+        self.gammas = []
+
+    def __repr__(self):
+        return (f"rows={self.rows} max_logit_rel_err={self.max_logit_err:.3e} max_conf_err={self.max_conf_err:.3e} "
+                f"id_near_tie={self.id_near_tie} gamma_near_tie={self.gamma_near_tie} mean_gamma={np.mean(self.gammas):.2f}")
+
+
+def lockstep(ctx, om, prompts, D, tau, steps, *, logit_tol, conf_tol, conf_fn=0, rule=0, overrides=None,
+             tie_gap=1e-3, bf16=False, check_logits=True, max_len=None):
+    """Run the HIP library and one oracle sequence per prompt step by step on the same token history.
+
+    After every step both sides commit the same tokens: the seeded override tokens on steps where `overrides`
+    supplies them, otherwise the oracle's own accepted prefix (through the library's NULL commit when the two
+    agree, through the override arguments otherwise).  Returns Stats; asserts the parity bar.
+    """
+    B = len(prompts)
+    V = om.vocab
+    max_len = max_len or max(len(p) for p in prompts) + steps * D + D
+    seqs = [orc.Seq(om, max_len) for _ in range(B)]
+    for s, p in zip(seqs, prompts):
+        s.prefill(np.asarray(p))
+    ctx.prefill(prompts)
+    ids = torch.empty(B, D, dtype=torch.int32, device="cuda")
+    cnt = torch.empty(B, dtype=torch.int32, device="cuda")
+    conf = torch.empty(B, D, dtype=torch.float32, device="cuda")
+    logits = torch.empty(B * D, V, dtype=torch.float32, device="cuda") if check_logits else None
+    st = Stats()
+    for t in range(steps):
+        ctx.decode_step(ids, cnt, conf, logits)
+        torch.cuda.synchronize()
+        g_ids, g_cnt, g_conf = ids.cpu().numpy(), cnt.cpu().numpy(), conf.cpu().numpy()
+        g_log = logits.cpu().numpy().reshape(B, D, V) if check_logits else None
+        agree = True
+        o_ids = np.zeros((B, D), np.int32)
+        o_cnt = np.zeros(B, np.int32)
+        for b in range(B):
+            lo, io, co, go = seqs[b].step(D, tau, rule, conf_fn)
+            o_ids[b], o_cnt[b] = io, go
+            for k in range(D):
+                st.rows += 1
+                srt = np.sort(lo[k])
+                gap, zmax = srt[-1] - srt[-2], np.max(np.abs(lo[k]))
+                err_abs = 0.0
+                if check_logits:
+                    err_abs = float(np.max(np.abs(g_log[b, k] - lo[k])))
+                    st.max_logit_err = max(st.max_logit_err, err_abs / zmax)
+                    assert err_abs / zmax <= logit_tol, f"step {t} seq {b} row {k}: logit rel err {err_abs / zmax:.3e}"
+                band = max(tie_gap, 2.0 * err_abs) if bf16 else tie_gap
+                if g_ids[b, k] != io[k]:
+                    assert gap < band, f"step {t} seq {b} row {k}: id {g_ids[b, k]} vs {io[k]}, top-2 gap {gap:.3e}, band {band:.3e}"
+                    st.id_near_tie += 1
+                    agree = False
+                cerr = abs(float(g_conf[b, k]) - float(co[k]))
+                st.max_conf_err = max(st.max_conf_err, cerr)
+                assert cerr <= conf_tol, f"step {t} seq {b} row {k}: conf {g_conf[b, k]} vs {co[k]}"
+            # the library's own gamma is the acceptance rule applied to its own confidences, bit for bit
+            assert int(g_cnt[b]) == orc.gamma(g_conf[b], tau, rule)
+            if int(g_cnt[b]) != go:
+                prods = np.cumprod(co.astype(np.float32)) if rule == 0 else co
+                assert np.min(np.abs(prods - np.float32(tau))) < max(1e-3, 2 * conf_tol if bf16 else 1e-3), \
+                    f"step {t} seq {b}: gamma {g_cnt[b]} vs {go}, conf {co}"
+                st.gamma_near_tie += 1
+                agree = False
+            st.gammas.append(go)
+        if overrides is not None and t < overrides[0].shape[0] and t % 2 == 1:
+            c_ids, c_cnt = overrides[0][t, :B].numpy().astype(np.int32), overrides[1][t, :B].numpy().astype(np.int32)
+            use_null = False
+        else:
+            c_ids, c_cnt = o_ids, o_cnt
+            use_null = agree
+        if use_null:
+            ctx.kv_commit()
+        else:
+            ctx.kv_commit(torch.tensor(c_ids, dtype=torch.int32).cuda().contiguous(), torch.tensor(c_cnt, dtype=torch.int32).cuda())
+        for b in range(B):
+            assert seqs[b].commit(c_ids[b], int(c_cnt[b])) == 0
+        n, c = ctx.get_lengths()
+        assert [int(v) for v in n] == [s.n for s in seqs] and [int(v) for v in c] == [s.c for s in seqs]
+    return st, seqs
