@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libsdlm.so")
-SOURCES = ["sdlm_api.hip", "kernels_generic.hip", "kernels_mfma.hip"]
+SOURCES = ["sdlm_api.hip", "kernels_generic.hip", "kernels_mfma.hip", "attn_mfma.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

@@ -1,0 +1,343 @@
+// Block-masked decode attention on the matrix cores (bf16 cache, head_dim 128, GQA).
+//
+// Work item = (row group, kv head, KV chunk).  A row group is a run of rows of one sequence (its pending causal
+// rows and its D block rows) small enough that rows x (query heads per kv head) <= 64 query vectors; all of them
+// consume each K/V tile once, so the cache is streamed from HBM once per (sequence, kv head, layer).
+//   scores   S^T[key, query] = K Q^T     v_mfma_f32_16x16x32_bf16, A = one 16-key K tile, B = 16 queries
+//   output   O^T[d, query]  += V^T P^T   same instruction, A = V^T of two tiles (32 keys), B = P^T
+// The cache tiles are stored in exactly the operand order of these instructions (see internal.hpp), so a
+// wavefront loads its operands global -> registers as contiguous 1 KB / 512 B runs; nothing is staged in LDS.
+// The mask of the method lives in registers: a pending row at position p sees cache keys [0, p]; a block row
+// sees cache keys [0, s) and the D keys of its own block (held in the sequence's staging tile).
+// The four wavefronts of a workgroup take alternate tile pairs of the chunk and merge through LDS; chunks of
+// one (group, head) are merged by a second small kernel when there is more than one.
+#include "mfma.hpp"
+
+namespace sdlm {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+
+constexpr int NQ = 4;     // 16-query tiles per work item
+constexpr int QMAX = NQ * 16;
+constexpr int HD = 128;
+
+struct AttnArgs {
+    const bf16_t *q;
+    bf16_t *out;
+    const bf16_t *pool;
+    KvGeom kg;
+    RowMeta rm;
+    SeqState st;
+    int Hq, G, D, chunk_pages, max_chunks;
+    float *part_o;      // [item][QMAX][HD]
+    float2 *part_ml;    // [item][QMAX]
+    float c;            // log2(e) / sqrt(d)
+};
+
+__device__ inline uint32_t pack_bf16(float lo, float hi)
+{
+    return (uint32_t)f_to_bf16(lo) | ((uint32_t)f_to_bf16(hi) << 16);
+}
+
+union Op8 { bf16x8 v; uint4 u; uint2 h[2]; uint32_t w[4]; };
+
+__global__ __launch_bounds__(256) void attn_mfma_k(AttnArgs a)
+{
+    const int g = blockIdx.x, hk = blockIdx.y, chunk = blockIdx.z;
+    if (g >= a.rm.counts[1]) return;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int ln = lane & 15, lg = lane >> 4;
+    const int row0 = a.rm.grp_row0[g], nrows = a.rm.grp_n[g], b = a.rm.grp_seq[g];
+    const int G = a.G, QR = nrows * G;
+
+    int lim_l = lane < nrows ? a.rm.lim[row0 + lane] : 0;
+    int blk_l = lane < nrows ? (a.rm.kind[row0 + lane] >= 0 ? 1 : 0) : 0;
+    int min_l = lane < nrows ? lim_l : 0x7fffffff;
+    for (int o = 32; o > 0; o >>= 1) {
+        lim_l = max(lim_l, __shfl_xor(lim_l, o));
+        blk_l |= __shfl_xor(blk_l, o);
+        min_l = min(min_l, __shfl_xor(min_l, o));
+    }
+    const int max_lim = lim_l, min_lim = min_l, any_blk = blk_l;
+    const int n_pages = (max_lim + PAGE - 1) / PAGE;
+    const int n_chunks = max(1, (n_pages + a.chunk_pages - 1) / a.chunk_pages);
+    if (chunk >= n_chunks) return;
+    const int c0 = chunk * a.chunk_pages, c1 = min(n_pages, c0 + a.chunk_pages);
+    const int n_cache = c1 - c0;
+    const int nv = n_cache + ((chunk == 0 && any_blk) ? 1 : 0);   // virtual tiles of this chunk; the last may be staging
+
+    // queries: B operands, lane (n = lane%16, group lg) holds q[32 kk + 8 lg .. +8] of query nq*16 + n
+    Op8 qop[NQ][4];
+    int lim_q[NQ], blk_q[NQ];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        int qi = nq * 16 + ln;
+        bool valid = qi < QR;
+        int rl = valid ? qi / G : 0, hg = valid ? qi % G : 0, row = row0 + rl;
+        lim_q[nq] = valid ? a.rm.lim[row] : 0;
+        blk_q[nq] = valid && a.rm.kind[row] >= 0;
+        const bf16_t *qp = a.q + ((size_t)row * a.Hq + hk * G + hg) * HD + lg * 8;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            if (valid) qop[nq][kk].u = *(const uint4 *)(qp + kk * 32);
+            else qop[nq][kk].u = make_uint4(0, 0, 0, 0);
+        }
+    }
+
+    f32x4 O[8][NQ];
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq) O[dt][nq] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run[NQ], l_run[NQ];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) { m_run[nq] = -INFINITY; l_run[nq] = 0.f; }
+
+    const int32_t *ptab = a.st.page_table + (size_t)b * a.kg.pages_per_seq;
+    const size_t tile_elems = 2 * PAGE * HD;
+    const int n_pairs = (nv + 1) / 2;
+    for (int pp = wave; pp < n_pairs; pp += 4) {
+        // the two virtual tiles of this pair; an absent second tile aliases the first and is masked out
+        int uA = 2 * pp, uB = 2 * pp + 1;
+        bool hasB = uB < nv;
+        bool stgA = uA >= n_cache, stgB = hasB && uB >= n_cache;
+        int pgA = stgA ? a.kg.staging_base + b : ptab[c0 + uA];
+        int pgB = !hasB ? pgA : (stgB ? a.kg.staging_base + b : ptab[c0 + uB]);
+        const bf16_t *tA = a.pool + ((size_t)pgA * a.kg.n_kv_heads + hk) * tile_elems;
+        const bf16_t *tB = a.pool + ((size_t)pgB * a.kg.n_kv_heads + hk) * tile_elems;
+        Op8 kA[4], kB[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            kA[kk].u = *(const uint4 *)(tA + (kk * 64 + lane) * 8);
+            kB[kk].u = *(const uint4 *)(tB + (kk * 64 + lane) * 8);
+        }
+        Op8 vop[8];
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+            vop[dt].h[0] = *(const uint2 *)(tA + PAGE * HD + (dt * 64 + lane) * 4);
+            vop[dt].h[1] = *(const uint2 *)(tB + PAGE * HD + (dt * 64 + lane) * 4);
+        }
+        // scores: lane (query n, group lg) gets keys 4 lg .. 4 lg + 3 of each tile
+        f32x4 sA[NQ], sB[NQ];
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq) {
+            sA[nq] = f32x4{0.f, 0.f, 0.f, 0.f};
+            sB[nq] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                sA[nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kA[kk].v, qop[nq][kk].v, sA[nq], 0, 0, 0);
+                sB[nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kB[kk].v, qop[nq][kk].v, sB[nq], 0, 0, 0);
+            }
+        }
+        const int keyA = (c0 + uA) * PAGE + lg * 4, keyB = (c0 + uB) * PAGE + lg * 4;
+        const bool fullA = !stgA && (c0 + uA + 1) * PAGE <= min_lim;
+        const bool fullB = hasB && !stgB && (c0 + uB + 1) * PAGE <= min_lim;
+        bool changed = false;
+        float m_new[NQ];
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                float x = sA[nq][v] * a.c, y = sB[nq][v] * a.c;
+                if (!fullA) {
+                    bool vis = stgA ? (blk_q[nq] && lg * 4 + v < a.D) : (keyA + v < lim_q[nq]);
+                    x = vis ? x : -INFINITY;
+                }
+                if (!fullB) {
+                    bool vis = hasB && (stgB ? (blk_q[nq] && lg * 4 + v < a.D) : (keyB + v < lim_q[nq]));
+                    y = vis ? y : -INFINITY;
+                }
+                sA[nq][v] = x; sB[nq][v] = y;
+                mx = fmaxf(mx, fmaxf(x, y));
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 16));
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            m_new[nq] = fmaxf(m_run[nq], mx);
+            changed |= m_new[nq] > m_run[nq];
+        }
+        if (__any(changed)) {
+#pragma unroll
+            for (int nq = 0; nq < NQ; ++nq) {
+                float corr = m_new[nq] == -INFINITY ? 1.f : exp2f(m_run[nq] - m_new[nq]);
+                l_run[nq] *= corr;
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt) O[dt][nq] *= corr;
+                m_run[nq] = m_new[nq];
+            }
+        }
+        Op8 pop[NQ];
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq) {
+            float mu = m_run[nq] == -INFINITY ? 0.f : m_run[nq];
+            float p[8];
+#pragma unroll
+            for (int v = 0; v < 4; ++v) { p[v] = exp2f(sA[nq][v] - mu); p[4 + v] = exp2f(sB[nq][v] - mu); }
+            l_run[nq] += (p[0] + p[1]) + (p[2] + p[3]) + (p[4] + p[5]) + (p[6] + p[7]);
+            pop[nq].w[0] = pack_bf16(p[0], p[1]); pop[nq].w[1] = pack_bf16(p[2], p[3]);
+            pop[nq].w[2] = pack_bf16(p[4], p[5]); pop[nq].w[3] = pack_bf16(p[6], p[7]);
+        }
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+            for (int nq = 0; nq < NQ; ++nq)
+                O[dt][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[dt].v, pop[nq].v, O[dt][nq], 0, 0, 0);
+    }
+
+    // merge the 4 wavefronts: common max per query, rescale, then a two-level sum through LDS into wavefront 0
+    __shared__ float sm_m[4][QMAX], sm_l[4][QMAX];
+    __shared__ __attribute__((aligned(16))) float sm_o[2][QMAX][HD + 4];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        l_run[nq] += __shfl_xor(l_run[nq], 16);
+        l_run[nq] += __shfl_xor(l_run[nq], 32);
+        if (lg == 0) sm_m[wave][nq * 16 + ln] = m_run[nq];
+    }
+    __syncthreads();
+    float M[NQ];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        int qi = nq * 16 + ln;
+        M[nq] = fmaxf(fmaxf(sm_m[0][qi], sm_m[1][qi]), fmaxf(sm_m[2][qi], sm_m[3][qi]));
+        float f = m_run[nq] == -INFINITY ? 0.f : exp2f(m_run[nq] - M[nq]);
+        if (lg == 0) sm_l[wave][qi] = l_run[nq] * f;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) O[dt][nq] *= f;
+    }
+    if (wave >= 2) {
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) *(f32x4 *)&sm_o[wave - 2][nq * 16 + ln][dt * 16 + lg * 4] = O[dt][nq];
+    }
+    __syncthreads();
+    if (wave < 2) {
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) O[dt][nq] += *(f32x4 *)&sm_o[wave][nq * 16 + ln][dt * 16 + lg * 4];
+    }
+    __syncthreads();
+    if (wave == 1) {
+#pragma unroll
+        for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) *(f32x4 *)&sm_o[0][nq * 16 + ln][dt * 16 + lg * 4] = O[dt][nq];
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    const bool single = n_chunks == 1;
+    const size_t item = ((size_t)g * a.kg.n_kv_heads + hk) * a.max_chunks + chunk;
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        int qi = nq * 16 + ln;
+        if (qi >= QR) continue;
+        float L = sm_l[0][qi] + sm_l[1][qi] + sm_l[2][qi] + sm_l[3][qi];
+        float inv = single ? 1.0f / L : 1.0f;
+        int rl = qi / G, hg = qi % G;
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+            f32x4 o = (O[dt][nq] + *(f32x4 *)&sm_o[0][qi][dt * 16 + lg * 4]) * inv;
+            int d4 = dt * 16 + lg * 4;
+            if (single) {
+                bf16_t *op = a.out + ((size_t)(row0 + rl) * a.Hq + hk * G + hg) * HD + d4;
+                *(uint2 *)op = make_uint2(pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3]));
+            } else {
+                *(f32x4 *)(a.part_o + (item * QMAX + qi) * HD + d4) = o;
+            }
+        }
+        if (!single && lg == 0) a.part_ml[item * QMAX + qi] = make_float2(M[nq], L);
+    }
+}
+
+// Merge the chunks of one (group, kv head): out = sum_c 2^{m_c - M} o_c / sum_c 2^{m_c - M} l_c.
+__global__ __launch_bounds__(256) void attn_combine_k(AttnArgs a)
+{
+    const int g = blockIdx.x, hk = blockIdx.y;
+    if (g >= a.rm.counts[1]) return;
+    const int row0 = a.rm.grp_row0[g], nrows = a.rm.grp_n[g];
+    const int QR = nrows * a.G;
+    int lim = 0;
+    for (int i = 0; i < nrows; ++i) lim = max(lim, a.rm.lim[row0 + i]);
+    const int n_pages = (lim + PAGE - 1) / PAGE;
+    const int n_chunks = max(1, (n_pages + a.chunk_pages - 1) / a.chunk_pages);
+    if (n_chunks == 1) return;   // the attention kernel wrote the final result itself
+    const size_t item0 = ((size_t)g * a.kg.n_kv_heads + hk) * a.max_chunks;
+    for (int e = threadIdx.x; e < QR * (HD / 4); e += 256) {
+        int qi = e / (HD / 4), d4 = (e % (HD / 4)) * 4;
+        float M = -INFINITY;
+        for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, a.part_ml[(item0 + c) * QMAX + qi].x);
+        float L = 0.f;
+        f32x4 o = {0.f, 0.f, 0.f, 0.f};
+        for (int c = 0; c < n_chunks; ++c) {
+            float2 ml = a.part_ml[(item0 + c) * QMAX + qi];
+            float f = ml.x == -INFINITY ? 0.f : exp2f(ml.x - M);
+            L += ml.y * f;
+            o += *(const f32x4 *)(a.part_o + ((item0 + c) * QMAX + qi) * HD + d4) * f;
+        }
+        float inv = 1.0f / L;
+        int rl = qi / a.G, hg = qi % a.G;
+        bf16_t *op = a.out + ((size_t)(row0 + rl) * a.Hq + hk * a.G + hg) * HD + d4;
+        *(uint2 *)op = make_uint2(pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv));
+    }
+}
+
+int mfma_group_rows(const sdlm_model_cfg *m)
+{
+    int G = m->n_q_heads / m->n_kv_heads;
+    int gr = QMAX / G;
+    return gr > GROUP_ROWS ? GROUP_ROWS : (gr < 1 ? 1 : gr);
+}
+
+// chunk size (in 16-key tiles) and chunk count for a launch over `groups` row groups
+static void chunking(const sdlm_model_cfg *m, int max_seq_len, int groups, int *chunk_pages, int *max_chunks)
+{
+    int pages = (max_seq_len + PAGE - 1) / PAGE;
+    long items = (long)groups * m->n_kv_heads;
+    int cp = 64;                                     // 1024 keys
+    while (cp > 8 && items * ((pages + cp - 1) / cp) < 512) cp >>= 1;
+    *chunk_pages = cp;
+    *max_chunks = (pages + cp - 1) / cp;
+}
+
+size_t mfma_attn_scratch_bytes(const sdlm_model_cfg *m, const sdlm_run_cfg *r, int max_rows)
+{
+    if (!mfma_supported(m)) return 256;
+    int gr = mfma_group_rows(m);
+    // decode: every sequence has at most ceil(2D / gr) groups; prefill: at most max_rows groups of >= 1 row, but
+    // then each group is short: bound both by the launch that needs the most (groups x chunks)
+    size_t worst = 0;
+    int cand[2] = {r->max_batch * ((2 * r->block_D + gr - 1) / gr), max_rows / gr + r->max_batch};
+    for (int i = 0; i < 2; ++i) {
+        int cp, mc;
+        chunking(m, r->max_seq_len, cand[i], &cp, &mc);
+        size_t items = (size_t)cand[i] * m->n_kv_heads * mc;
+        worst = items > worst ? items : worst;
+    }
+    return worst * ((size_t)QMAX * HD * 4 + QMAX * 8) + 256;
+}
+
+void launch_attn_mfma(hipStream_t s, const sdlm_model_cfg *m, int max_seq_len, const void *q, void *out, const void *pool_layer,
+                      const KvGeom &kg, const RowMeta &rm, const SeqState &st, int D, int max_groups, void *scratch, size_t scratch_bytes)
+{
+    AttnArgs a;
+    a.q = (const bf16_t *)q; a.out = (bf16_t *)out; a.pool = (const bf16_t *)pool_layer;
+    a.kg = kg; a.rm = rm; a.st = st; a.Hq = m->n_q_heads; a.G = m->n_q_heads / m->n_kv_heads; a.D = D;
+    chunking(m, max_seq_len, max_groups, &a.chunk_pages, &a.max_chunks);
+    const int pages = (max_seq_len + PAGE - 1) / PAGE;
+    size_t items = (size_t)max_groups * kg.n_kv_heads * a.max_chunks;
+    while (a.max_chunks > 1 && items * ((size_t)QMAX * HD * 4 + QMAX * 8) > scratch_bytes) {   // coarser chunks until the partials fit
+        a.chunk_pages *= 2;
+        a.max_chunks = (pages + a.chunk_pages - 1) / a.chunk_pages;
+        items = (size_t)max_groups * kg.n_kv_heads * a.max_chunks;
+    }
+    a.part_o = (float *)scratch;
+    a.part_ml = (float2 *)((char *)scratch + items * QMAX * HD * 4);
+    a.c = 1.4426950408889634f / sqrtf((float)HD);
+    hipLaunchKernelGGL(attn_mfma_k, dim3(max_groups, kg.n_kv_heads, a.max_chunks), dim3(256), 0, s, a);
+    if (a.max_chunks > 1)
+        hipLaunchKernelGGL(attn_combine_k, dim3(max_groups, kg.n_kv_heads), dim3(256), 0, s, a);
+}
+
+}  // namespace sdlm

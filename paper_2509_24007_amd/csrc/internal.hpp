@@ -86,13 +86,13 @@ struct GemmArgs {
     float scale;
 };
 
-void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id);
+void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows);
 void launch_embed(hipStream_t s, int dtype, float *x, const void *E, const RowMeta &rm, int max_rows, int h);
 void launch_rmsnorm(hipStream_t s, int dtype, void *out, const float *x, const void *g, int h, float eps,
                     const int32_t *row_index, const int32_t *p_count, int max_rows);
 void launch_gemm_generic(hipStream_t s, int dtype, int epi, const GemmArgs &a);
-void launch_rope_scatter(hipStream_t s, int dtype, const float *qkv, void *q_out, void *pool_layer, const KvGeom &kg,
-                         const RowMeta &rm, const SeqState &st, const float2 *rope, int n_q_heads, int max_rows);
+void launch_rope_scatter(hipStream_t s, int dtype, const float *qkv, int n_slabs, size_t slab_stride, void *q_out, void *pool_layer,
+                         const KvGeom &kg, const RowMeta &rm, const SeqState &st, const float2 *rope, int n_q_heads, int max_rows);
 void launch_attn_generic(hipStream_t s, int dtype, const void *q, void *out, const void *pool_layer, const KvGeom &kg,
                          const RowMeta &rm, const SeqState &st, int n_q_heads, int D, int max_rows);
 void launch_lm_reduce(hipStream_t s, const float *logits, int V, int32_t *ids, float *conf, int conf_fn,

@@ -10,7 +10,7 @@ namespace sdlm {
 // Rows of a decode step, per sequence: the pending tokens (positions c..n-1, causal), then the block
 // [x_last, [m] x (D-1)] at positions n-1 .. n+D-2 (block definition, Sec. 3.2).  A block row may see the cache
 // below position s = n-1 only; the causal copy of x_last at s is for later steps.
-__global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mask_id)
+__global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mask_id, int gr)
 {
     __shared__ int row0[1025], grp0[1025];
     if (threadIdx.x == 0) {
@@ -19,7 +19,7 @@ __global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mas
             row0[b] = r; grp0[b] = g;
             int rows = st.n[b] - st.c[b] + D;
             r += rows;
-            g += (rows + GROUP_ROWS - 1) / GROUP_ROWS;
+            g += (rows + gr - 1) / gr;
         }
         row0[B] = r; grp0[B] = g;
         rm.counts[0] = r; rm.counts[1] = g; rm.counts[2] = B * D; rm.counts[3] = 0;
@@ -37,17 +37,17 @@ __global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mas
             rm.blk_row[b * D + j] = r;
         }
         int rows = p + D, g = grp0[b];
-        for (int o = 0; o < rows; o += GROUP_ROWS, ++g) {
+        for (int o = 0; o < rows; o += gr, ++g) {
             rm.grp_row0[g] = row0[b] + o;
-            rm.grp_n[g] = min(GROUP_ROWS, rows - o);
+            rm.grp_n[g] = min(gr, rows - o);
             rm.grp_seq[g] = b;
         }
     }
 }
 
-void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id)
+void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows)
 {
-    hipLaunchKernelGGL(assemble_decode_k, dim3(1), dim3(256), 0, s, st, rm, B, D, mask_id);
+    hipLaunchKernelGGL(assemble_decode_k, dim3(1), dim3(256), 0, s, st, rm, B, D, mask_id, group_rows);
 }
 
 // ------------------------------------------------------------------------------------------------ embedding
@@ -176,17 +176,22 @@ void launch_gemm_generic(hipStream_t s, int dtype, int epi, const GemmArgs &a)
 }
 
 // ------------------------------------------------------------------------------------------------ RoPE + K/V placement
-// qkv: raw projections [R, (Hq + 2 Hkv) d] fp32.  Queries and keys are rotated at the row's position (rotate-half
+// qkv: raw projections [R, (Hq + 2 Hkv) d] fp32, given as n_slabs partial sums that are added in order.  Queries and keys are rotated at the row's position (rotate-half
 // pairing i <-> i + d/2).  A pending row's K/V go to the cache slot of its position: they are final.  A block
 // row's K/V go to its sequence's staging tile, slot = block index: they are never cached.
 template <typename T>
-__global__ __launch_bounds__(256) void rope_scatter_k(const float *qkv, T *q_out, T *pool, KvGeom kg, RowMeta rm, SeqState st,
-                                                      const float2 *rope, int Hq)
+__global__ __launch_bounds__(256) void rope_scatter_k(const float *qkv, int n_slabs, size_t slab_stride, T *q_out, T *pool, KvGeom kg,
+                                                      RowMeta rm, SeqState st, const float2 *rope, int Hq)
 {
     int r = blockIdx.x;
     if (r >= rm.counts[0]) return;
     const int d = kg.head_dim, half = d >> 1, Hk = kg.n_kv_heads, nq = Hq * d, nk = Hk * d;
     const float *row = qkv + (size_t)r * (nq + 2 * nk);
+    auto val = [&](int col) {
+        float v = row[col];
+        for (int sl = 1; sl < n_slabs; ++sl) v += row[sl * slab_stride + col];
+        return v;
+    };
     const int pos = rm.pos[r], kind = rm.kind[r], b = rm.seq[r];
     const float2 *cs = rope + (size_t)pos * half;
     int page, slot;
@@ -195,7 +200,7 @@ __global__ __launch_bounds__(256) void rope_scatter_k(const float *qkv, T *q_out
     for (int e = threadIdx.x; e < Hq * half; e += 256) {
         int hq = e / half, i = e % half;
         float2 t = cs[i];
-        float x0 = row[hq * d + i], x1 = row[hq * d + i + half];
+        float x0 = val(hq * d + i), x1 = val(hq * d + i + half);
         q_out[(size_t)r * nq + hq * d + i] = from_f<T>(x0 * t.x - x1 * t.y);
         q_out[(size_t)r * nq + hq * d + i + half] = from_f<T>(x1 * t.x + x0 * t.y);
     }
@@ -203,22 +208,22 @@ __global__ __launch_bounds__(256) void rope_scatter_k(const float *qkv, T *q_out
     for (int e = threadIdx.x; e < Hk * half; e += 256) {
         int hk = e / half, i = e % half;
         float2 t = cs[i];
-        const float *kr = row + nq + hk * d, *vr = row + nq + nk + hk * d;
+        const int kc = nq + hk * d, vc = nq + nk + hk * d;
         T *tile = pool + kg.tile(page, hk);
         T *Kb = tile, *Vb = tile + PAGE * d;
-        float x0 = kr[i], x1 = kr[i + half];
+        float x0 = val(kc + i), x1 = val(kc + i + half);
         Kb[k_off(slot, i)] = from_f<T>(x0 * t.x - x1 * t.y);
         Kb[k_off(slot, i + half)] = from_f<T>(x1 * t.x + x0 * t.y);
-        Vb[v_off(slot, i)] = from_f<T>(vr[i]);
-        Vb[v_off(slot, i + half)] = from_f<T>(vr[i + half]);
+        Vb[v_off(slot, i)] = from_f<T>(val(vc + i));
+        Vb[v_off(slot, i + half)] = from_f<T>(val(vc + i + half));
     }
 }
 
-void launch_rope_scatter(hipStream_t s, int dtype, const float *qkv, void *q_out, void *pool_layer, const KvGeom &kg,
-                         const RowMeta &rm, const SeqState &st, const float2 *rope, int n_q_heads, int max_rows)
+void launch_rope_scatter(hipStream_t s, int dtype, const float *qkv, int n_slabs, size_t slab_stride, void *q_out, void *pool_layer,
+                         const KvGeom &kg, const RowMeta &rm, const SeqState &st, const float2 *rope, int n_q_heads, int max_rows)
 {
-    if (dtype == 0) hipLaunchKernelGGL(rope_scatter_k<float>, dim3(max_rows), dim3(256), 0, s, qkv, (float *)q_out, (float *)pool_layer, kg, rm, st, rope, n_q_heads);
-    else hipLaunchKernelGGL(rope_scatter_k<bf16_t>, dim3(max_rows), dim3(256), 0, s, qkv, (bf16_t *)q_out, (bf16_t *)pool_layer, kg, rm, st, rope, n_q_heads);
+    if (dtype == 0) hipLaunchKernelGGL(rope_scatter_k<float>, dim3(max_rows), dim3(256), 0, s, qkv, n_slabs, slab_stride, (float *)q_out, (float *)pool_layer, kg, rm, st, rope, n_q_heads);
+    else hipLaunchKernelGGL(rope_scatter_k<bf16_t>, dim3(max_rows), dim3(256), 0, s, qkv, n_slabs, slab_stride, (bf16_t *)q_out, (bf16_t *)pool_layer, kg, rm, st, rope, n_q_heads);
 }
 
 // ------------------------------------------------------------------------------------------------ attention

@@ -1,15 +1,426 @@
-// Matrix-core kernels of the bf16 mode.
+// Matrix-core (MFMA) GEMMs of the bf16 mode: the QKV / O / gate-up / down projections and the LM head with its
+// fused vocabulary reduction.  These are the path's only true dense contractions.
+//
+// Y[r, n] = sum_k X[r, k] W[n, k], R activation rows (8 .. 2048) against N weight rows: every weight byte is
+// needed exactly once per step, so the kernels are organised around streaming W from HBM.
+//   * W is repacked once (sdlm_init_weights) into the operand order of v_mfma_f32_32x32x16_bf16: tile (n/32,
+//     k/16) is 64 lanes x 8 bf16 = 1 KB contiguous and the tiles of one 32-row band follow each other along k,
+//     so a wavefront's operand stream is a plain contiguous run, loaded global -> registers with 16-byte loads
+//     and never staged in LDS (no other wavefront of the workgroup needs the same weights).
+//   * The weight tile is the A operand (M = 32 output features), the activation rows are the B operand
+//     (N = 32 rows).  A workgroup is 4 wavefronts; each owns NT bands of output features and all of them
+//     share the MT*32 activation rows of the workgroup, which are staged in LDS (64-deep k slices, double
+//     buffered, rows padded to 144 bytes so that the 16-byte operand reads do not collide on banks).
+//   * Skinny problems (few rows, few output features) are split along k; the partial sums go to a scratch
+//     slab per split and are added in a fixed order by the consumer, so results do not depend on timing.
+//   * Workgroup ids are remapped so that the row blocks of one weight band run on the same XCD and share its L2.
 #include "mfma.hpp"
 
 namespace sdlm {
 
-bool mfma_supported(const sdlm_model_cfg *) { return false; }
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+constexpr int XS_STRIDE = 72;   // bf16 elements per LDS row of the activation slice (64 + 8 padding)
+
+bool mfma_supported(const sdlm_model_cfg *m)
+{
+    return m->dtype == 1 && m->head_dim == 128 && m->hidden % 64 == 0 && m->ffn % 64 == 0 &&
+           (m->n_q_heads * m->head_dim) % 64 == 0 && m->n_q_heads / m->n_kv_heads <= 64;
+}
 size_t mfma_pad_n(size_t N) { return (N + 31) / 32 * 32; }
 size_t mfma_packed_elems(bool packed, size_t N, size_t K) { return (packed ? mfma_pad_n(N) : N) * K; }
-size_t mfma_attn_scratch_bytes(const sdlm_model_cfg *, const sdlm_run_cfg *, int) { return 256; }
-void launch_pack_mfma(hipStream_t, void *, const void *, int, int, int, int, int) {}
-void launch_gemm_mfma(hipStream_t, int, const GemmArgs &) {}
-void launch_attn_mfma(hipStream_t, const void *, void *, const void *, const KvGeom &, const RowMeta &, const SeqState &, int, int, int, void *) {}
-void launch_lmhead_mfma(hipStream_t, const void *, const void *, int, int, int, float, int, float *, void *, int32_t *, float *) {}
+
+// ------------------------------------------------------------------------------------------------ weight packing
+// dst tile order: [n/32][k/16][lane][8] with lane = (n % 32) + 32 * ((k % 16) / 8).
+__global__ void pack_mfma_k(bf16_t *dst, const bf16_t *src, int N, int K, int dst_row0, int interleave)
+{
+    const int KS = K / 16;
+    size_t g = (size_t)blockIdx.x * blockDim.x + threadIdx.x;   // one 8-element group
+    size_t total = (size_t)((N + 31) / 32) * KS * 64;
+    if (g >= total) return;
+    int lane = (int)(g & 63);
+    size_t t = g >> 6;
+    int ks = (int)(t % KS), nt = (int)(t / KS);
+    int n = nt * 32 + (lane & 31), k = ks * 16 + (lane >> 5) * 8;
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (n < N) v = *(const uint4 *)(src + (size_t)n * K + k);
+    int dtile = interleave == 0 ? dst_row0 / 32 + nt : 2 * nt + (interleave - 1);
+    *(uint4 *)(dst + (((size_t)dtile * KS + ks) * 64 + lane) * 8) = v;
+}
+
+void launch_pack_mfma(hipStream_t s, void *dst, const void *src, int N, int K, int dst_row0, int, int interleave)
+{
+    size_t total = (size_t)((N + 31) / 32) * (K / 16) * 64;
+    hipLaunchKernelGGL(pack_mfma_k, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (bf16_t *)dst, (const bf16_t *)src, N, K, dst_row0, interleave);
+}
+
+// ------------------------------------------------------------------------------------------------ GEMM
+struct MfmaArgs {
+    const bf16_t *X, *Wp, *bias;
+    float *Yf;          // STORE_F32 / RESID destination, or split-k slabs
+    bf16_t *Yt;         // SWIGLU destination
+    float *logits;      // LM head: optional [rows, N] logits
+    float4 *lm_part;    // LM head: [n_blocks][max_rows] partial (max, sum, entropy sum, argmax bits)
+    const int32_t *pR;
+    int max_rows, N, K, n_tiles, n_blocks, m_blocks, splits, stages_per_split, n_out;   // n_out: row length of the destination
+    size_t slab;        // elements between split-k slabs
+    float scale;
+};
+
+enum { EPI_LMHEAD = 4 };
+
+__device__ inline float silu_f(float v) { return v / (1.0f + __expf(-v)); }
+
+template <int MT, int NT, int EPI>
+__global__ __launch_bounds__(256) void gemm_mfma_k(MfmaArgs a)
+{
+    __shared__ __attribute__((aligned(16))) bf16_t Xs[2][MT * 32][XS_STRIDE];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int R = min(*a.pR, a.max_rows);
+    // workgroup id -> tile: ids that land on one XCD (id % 8) get consecutive tiles
+    const int per = gridDim.x >> 3;
+    const int t = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+    if (t >= a.n_blocks * a.m_blocks * a.splits) return;
+    const int mblk = t % a.m_blocks, split = (t / a.m_blocks) % a.splits, nblk = t / (a.m_blocks * a.splits);
+    const int m0 = mblk * MT * 32;
+    if (m0 >= R) return;
+    const int KS = a.K >> 4, S = a.K >> 6;
+    const int s_begin = split * a.stages_per_split, s_end = min(S, s_begin + a.stages_per_split);
+    if (s_begin >= s_end) return;
+
+    const bf16_t *wp[NT];
+    int ntile[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        ntile[nt] = (nblk * 4 + wave) * NT + nt;
+        int tl = min(ntile[nt], a.n_tiles - 1);
+        wp[nt] = a.Wp + ((size_t)tl * KS) * 512 + lane * 8;
+    }
+    // activation slice: MT*32 rows x 64 k = MT*256 16-byte chunks, MT per thread
+    const int xrow = tid >> 3, xchunk = tid & 7;
+    const bf16_t *xp[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) xp[i] = a.X + (size_t)min(m0 + i * 32 + xrow, R - 1) * a.K + xchunk * 8;
+
+    f32x16 acc[NT][MT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[nt][mt][v] = 0.f;
+
+    bf16x8 wc[NT][4], wn[NT][4];
+    uint4 xr[MT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) wc[nt][ks] = *(const bf16x8 *)(wp[nt] + ((size_t)s_begin * 4 + ks) * 512);
+#pragma unroll
+    for (int i = 0; i < MT; ++i) xr[i] = *(const uint4 *)(xp[i] + (size_t)s_begin * 64);
+#pragma unroll
+    for (int i = 0; i < MT; ++i) *(uint4 *)&Xs[0][i * 32 + xrow][xchunk * 8] = xr[i];
+    __syncthreads();
+
+    const int brow = lane & 31, bk = (lane >> 5) * 8;
+    for (int s = s_begin; s < s_end; ++s) {
+        const int buf = (s - s_begin) & 1;
+        const bool more = s + 1 < s_end;
+        if (more) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) wn[nt][ks] = *(const bf16x8 *)(wp[nt] + ((size_t)(s + 1) * 4 + ks) * 512);
+#pragma unroll
+            for (int i = 0; i < MT; ++i) xr[i] = *(const uint4 *)(xp[i] + (size_t)(s + 1) * 64);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                bf16x8 b = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][ks * 16 + bk];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[nt][ks], b, acc[nt][mt], 0, 0, 0);
+            }
+        if (more) {
+#pragma unroll
+            for (int i = 0; i < MT; ++i) *(uint4 *)&Xs[buf ^ 1][i * 32 + xrow][xchunk * 8] = xr[i];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) wc[nt][ks] = wn[nt][ks];
+        }
+        __syncthreads();
+    }
+
+    // accumulator element v of lane l: output feature 8*(v/4) + 4*(l/32) + v%4 of the tile, activation row l%32
+    const int fbase = (lane >> 5) * 4;
+    if (EPI == EPI_STORE_F32 || EPI == EPI_RESID) {
+        float *dst = a.Yf + (a.splits > 1 ? (size_t)split * a.slab : 0);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            if (ntile[nt] >= a.n_tiles) continue;
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                int r = m0 + mt * 32 + brow;
+                if (r >= R) continue;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    int n = ntile[nt] * 32 + q * 8 + fbase;
+                    if (n >= a.N) continue;
+                    float4 v = make_float4(acc[nt][mt][q * 4], acc[nt][mt][q * 4 + 1], acc[nt][mt][q * 4 + 2], acc[nt][mt][q * 4 + 3]);
+                    float4 *p = (float4 *)(dst + (size_t)r * a.n_out + n);
+                    if (EPI == EPI_STORE_F32) {
+                        if (a.bias && split == 0) {
+                            v.x += bf16_to_f(a.bias[n]); v.y += bf16_to_f(a.bias[n + 1]);
+                            v.z += bf16_to_f(a.bias[n + 2]); v.w += bf16_to_f(a.bias[n + 3]);
+                        }
+                        *p = v;
+                    } else if (a.splits > 1) {
+                        *p = v;
+                    } else {
+                        float4 o = *p;
+                        o.x += v.x; o.y += v.y; o.z += v.z; o.w += v.w;
+                        *p = o;
+                    }
+                }
+            }
+        }
+    } else if (EPI == EPI_SWIGLU) {
+        // the fused matrix alternates 32-row tiles of gate and up: tiles (2j, 2j+1) belong to features 32j..32j+31
+        static_assert(EPI != EPI_SWIGLU || NT == 2, "gate and up tiles must sit in one wavefront");
+        const int j = ntile[0] >> 1;
+        if (ntile[0] + 1 < a.n_tiles + 1 && ntile[0] < a.n_tiles) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                int r = m0 + mt * 32 + brow;
+                if (r >= R) continue;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    int n = j * 32 + q * 8 + fbase;
+                    if (n >= a.N) continue;
+                    bf16_t o[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) o[e] = f_to_bf16(silu_f(acc[0][mt][q * 4 + e]) * acc[NT - 1][mt][q * 4 + e]);
+                    *(uint2 *)(a.Yt + (size_t)r * a.n_out + n) = make_uint2(o[0] | ((uint32_t)o[1] << 16), o[2] | ((uint32_t)o[3] << 16));
+                }
+            }
+        }
+    } else {
+        // LM head: logits of this workgroup's 128*NT vocabulary entries -> per-row (max, argmax, sum exp, entropy sum)
+        __shared__ float sm_m[4][MT * 32];
+        __shared__ int sm_a[4][MT * 32];
+        __shared__ float sm_s[4][MT * 32], sm_e[4][MT * 32];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            const int r = m0 + mt * 32 + brow;
+            float m = -INFINITY;
+            int arg = 0x7fffffff;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    int n = ntile[nt] * 32 + (v >> 2) * 8 + fbase + (v & 3);
+                    float z = acc[nt][mt][v] * a.scale;
+                    acc[nt][mt][v] = z;
+                    if (n < a.N) {
+                        if (a.logits && r < R) a.logits[(size_t)r * a.N + n] = z;
+                        if (z > m || (z == m && n < arg)) { m = z; arg = n; }
+                    }
+                }
+            float om = __shfl_xor(m, 32);
+            int oa = __shfl_xor(arg, 32);
+            if (om > m || (om == m && oa < arg)) { m = om; arg = oa; }
+            if (lane < 32) { sm_m[wave][mt * 32 + lane] = m; sm_a[wave][mt * 32 + lane] = arg; }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            float m = sm_m[0][mt * 32 + brow];
+#pragma unroll
+            for (int w = 1; w < 4; ++w) m = fmaxf(m, sm_m[w][mt * 32 + brow]);
+            float S = 0.f, E = 0.f;
+            if (m > -INFINITY) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        int n = ntile[nt] * 32 + (v >> 2) * 8 + fbase + (v & 3);
+                        if (n < a.N) {
+                            float dlt = acc[nt][mt][v] - m, e = __expf(dlt);
+                            S += e;
+                            E += e * dlt;
+                        }
+                    }
+            }
+            S += __shfl_xor(S, 32);
+            E += __shfl_xor(E, 32);
+            if (lane < 32) { sm_s[wave][mt * 32 + lane] = S; sm_e[wave][mt * 32 + lane] = E; }
+        }
+        __syncthreads();
+        for (int i = tid; i < MT * 32; i += 256) {
+            int r = m0 + i;
+            if (r >= R) continue;
+            float m = sm_m[0][i];
+            int arg = sm_a[0][i];
+            float S = sm_s[0][i], E = sm_e[0][i];
+            for (int w = 1; w < 4; ++w) {
+                if (sm_m[w][i] > m || (sm_m[w][i] == m && sm_a[w][i] < arg)) { m = sm_m[w][i]; arg = sm_a[w][i]; }
+                S += sm_s[w][i];
+                E += sm_e[w][i];
+            }
+            a.lm_part[(size_t)nblk * a.max_rows + r] = make_float4(m, S, E, __int_as_float(arg));
+        }
+    }
+}
+
+// x[r, :] += sum over split slabs (fixed order)
+__global__ __launch_bounds__(256) void reduce_slabs_k(float *x, const float *part, int splits, size_t slab, int n, const int32_t *pR, int max_rows)
+{
+    int r = blockIdx.x;
+    if (r >= min(*pR, max_rows)) return;
+    for (int c = threadIdx.x * 4; c < n; c += 1024) {
+        float4 o = *(float4 *)(x + (size_t)r * n + c);
+        for (int s = 0; s < splits; ++s) {
+            float4 v = *(const float4 *)(part + s * slab + (size_t)r * n + c);
+            o.x += v.x; o.y += v.y; o.z += v.z; o.w += v.w;
+        }
+        *(float4 *)(x + (size_t)r * n + c) = o;
+    }
+}
+
+// Combine the LM head's per-block partials of one row: overall arg-max (lowest index on ties), and with
+// M = max_i m_i:  S = sum_i S_i e^{m_i - M},  E = sum_i e^{m_i - M} (E_i + S_i (m_i - M)).
+__global__ __launch_bounds__(256) void lm_combine_k(const float4 *part, int n_blocks, int max_rows, const int32_t *p_rows, int V, int conf_fn,
+                                                    int32_t *ids, float *conf)
+{
+    int r = blockIdx.x;
+    if (r >= min(*p_rows, max_rows)) return;
+    __shared__ float sm[4];
+    __shared__ int sa[4];
+    __shared__ float red[4];
+    float m = -INFINITY;
+    int arg = 0x7fffffff;
+    for (int i = threadIdx.x; i < n_blocks; i += 256) {
+        float4 p = part[(size_t)i * max_rows + r];
+        int a = __float_as_int(p.w);
+        if (p.x > m || (p.x == m && a < arg)) { m = p.x; arg = a; }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+        float om = __shfl_xor(m, o);
+        int oa = __shfl_xor(arg, o);
+        if (om > m || (om == m && oa < arg)) { m = om; arg = oa; }
+    }
+    if ((threadIdx.x & 63) == 0) { sm[threadIdx.x >> 6] = m; sa[threadIdx.x >> 6] = arg; }
+    __syncthreads();
+    m = sm[0]; arg = sa[0];
+    for (int w = 1; w < 4; ++w)
+        if (sm[w] > m || (sm[w] == m && sa[w] < arg)) { m = sm[w]; arg = sa[w]; }
+    float S = 0.f, E = 0.f;
+    for (int i = threadIdx.x; i < n_blocks; i += 256) {
+        float4 p = part[(size_t)i * max_rows + r];
+        float dm = p.x - m, f = __expf(dm);
+        S += p.y * f;
+        E += f * (p.z + p.y * dm);
+    }
+    for (int o = 32; o > 0; o >>= 1) { S += __shfl_xor(S, o); E += __shfl_xor(E, o); }
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) { sm[threadIdx.x >> 6] = S; red[threadIdx.x >> 6] = E; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        S = sm[0] + sm[1] + sm[2] + sm[3];
+        E = red[0] + red[1] + red[2] + red[3];
+        ids[r] = arg;
+        conf[r] = conf_fn == 0 ? 1.0f / S : 1.0f - (logf(S) - E / S) / logf((float)V);
+    }
+}
+
+// ------------------------------------------------------------------------------------------------ launch policy
+struct TileChoice { int MT, NT, splits; };
+
+static TileChoice choose(int epi, int rows, int N, int K, size_t slab_room_floats)
+{
+    TileChoice c;
+    c.MT = rows <= 32 ? 1 : rows <= 64 ? 2 : 4;
+    c.NT = 2;
+    if (epi != EPI_SWIGLU && epi != EPI_LMHEAD) {
+        int mb = (rows + c.MT * 32 - 1) / (c.MT * 32);
+        if ((long)((N + 255) / 256) * mb < 256) c.NT = 1;
+    }
+    c.splits = 1;
+    if (epi == EPI_STORE_F32 || epi == EPI_RESID) {
+        int bn = 128 * c.NT, mb = (rows + c.MT * 32 - 1) / (c.MT * 32);
+        long wgs = (long)((N + bn - 1) / bn) * mb;
+        int S = K / 64, want = (int)((512 + wgs - 1) / wgs);
+        int cap_k = S / 4 > 0 ? S / 4 : 1;                             // at least 4 stages (256 deep) per split
+        long cap_m = (long)(slab_room_floats / ((size_t)rows * N));    // slabs must fit the scratch area
+        int sp = want;
+        if (sp > cap_k) sp = cap_k;
+        if (sp > cap_m) sp = (int)cap_m;
+        if (sp > 16) sp = 16;
+        if (sp < 1) sp = 1;
+        if ((size_t)rows * N * 4 * sp > (size_t)8 << 20 && wgs >= 128) sp = sp > 2 ? 2 : sp;   // many rows: slab traffic outweighs the gain
+        c.splits = sp;
+    }
+    return c;
+}
+
+template <int EPI>
+static void launch_cfg(hipStream_t s, const TileChoice &c, MfmaArgs &a)
+{
+    a.n_blocks = (a.n_tiles + 4 * c.NT - 1) / (4 * c.NT);
+    a.m_blocks = (a.max_rows + c.MT * 32 - 1) / (c.MT * 32);
+    a.splits = c.splits;
+    int S = a.K / 64;
+    a.stages_per_split = (S + c.splits - 1) / c.splits;
+    int tiles = a.n_blocks * a.m_blocks * a.splits;
+    dim3 grid((tiles + 7) / 8 * 8), block(256);
+#define SDLM_GO(MT_, NT_) hipLaunchKernelGGL((gemm_mfma_k<MT_, NT_, EPI>), grid, block, 0, s, a)
+    if (EPI == EPI_SWIGLU || EPI == EPI_LMHEAD || c.NT == 2) {
+        if (c.MT == 1) SDLM_GO(1, 2); else if (c.MT == 2) SDLM_GO(2, 2); else SDLM_GO(4, 2);
+    } else {
+        if (EPI == EPI_STORE_F32 || EPI == EPI_RESID) {
+            if (c.MT == 1) hipLaunchKernelGGL((gemm_mfma_k<1, 1, (EPI == EPI_STORE_F32 || EPI == EPI_RESID) ? EPI : EPI_RESID>), grid, block, 0, s, a);
+            else if (c.MT == 2) hipLaunchKernelGGL((gemm_mfma_k<2, 1, (EPI == EPI_STORE_F32 || EPI == EPI_RESID) ? EPI : EPI_RESID>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((gemm_mfma_k<4, 1, (EPI == EPI_STORE_F32 || EPI == EPI_RESID) ? EPI : EPI_RESID>), grid, block, 0, s, a);
+        }
+    }
+#undef SDLM_GO
+}
+
+int launch_gemm_mfma(hipStream_t s, int epi, const GemmArgs &g, float *slabs, size_t slab_room_floats)
+{
+    MfmaArgs a{};
+    a.X = (const bf16_t *)g.X; a.Wp = (const bf16_t *)g.W; a.bias = (const bf16_t *)g.bias;
+    a.Yf = g.Yf; a.Yt = (bf16_t *)g.Yt; a.pR = g.pR; a.max_rows = g.max_rows; a.N = g.N; a.K = g.K; a.scale = g.scale;
+    a.n_out = g.N;
+    a.n_tiles = epi == EPI_SWIGLU ? 2 * (int)(mfma_pad_n(g.N) / 32) : (int)(mfma_pad_n(g.N) / 32);
+    TileChoice c = choose(epi, g.max_rows, g.N, g.K, slab_room_floats);
+    a.slab = (size_t)g.max_rows * g.N;
+    if (c.splits > 1) a.Yf = slabs;
+    switch (epi) {
+    case EPI_STORE_F32: launch_cfg<EPI_STORE_F32>(s, c, a); break;
+    case EPI_RESID: launch_cfg<EPI_RESID>(s, c, a); break;
+    default: launch_cfg<EPI_SWIGLU>(s, c, a); break;
+    }
+    if (c.splits > 1 && epi == EPI_RESID)
+        hipLaunchKernelGGL(reduce_slabs_k, dim3(g.max_rows), dim3(256), 0, s, g.Yf, slabs, c.splits, a.slab, g.N, g.pR, g.max_rows);
+    return c.splits;   // for STORE_F32 the caller's consumer adds the slabs
+}
+
+void launch_lmhead_mfma(hipStream_t s, const void *xhat, const void *w_packed, const int32_t *p_rows, int max_rows, int V, int h, float scale,
+                        int conf_fn, float *logits_out, void *scratch, int32_t *ids, float *conf)
+{
+    MfmaArgs a{};
+    a.X = (const bf16_t *)xhat; a.Wp = (const bf16_t *)w_packed; a.pR = p_rows; a.max_rows = max_rows; a.N = V; a.K = h; a.scale = scale;
+    a.n_out = V; a.logits = logits_out; a.lm_part = (float4 *)scratch;
+    a.n_tiles = (int)(mfma_pad_n(V) / 32);
+    TileChoice c = choose(EPI_LMHEAD, max_rows, V, h, 0);
+    launch_cfg<EPI_LMHEAD>(s, c, a);
+    hipLaunchKernelGGL(lm_combine_k, dim3(max_rows), dim3(256), 0, s, (const float4 *)scratch, a.n_blocks, max_rows, p_rows, V, conf_fn, ids, conf);
+}
+
+size_t mfma_lm_scratch_bytes(int V, int max_rows) { return (size_t)((mfma_pad_n(V) / 32 + 7) / 8) * max_rows * sizeof(float4); }
 
 }  // namespace sdlm

@@ -10,17 +10,23 @@ bool mfma_supported(const sdlm_model_cfg *m);
 size_t mfma_pad_n(size_t N);
 // Elements a packed [N, K] matrix occupies (N * K when `packed` is false).
 size_t mfma_packed_elems(bool packed, size_t N, size_t K);
-// Bytes of scratch the split-KV attention and the LM-head partials need.
+// Bytes of scratch the split-KV attention needs for its per-chunk partial results.
 size_t mfma_attn_scratch_bytes(const sdlm_model_cfg *m, const sdlm_run_cfg *r, int max_rows);
+// Bytes of scratch for the LM head's per-vocabulary-block partials.
+size_t mfma_lm_scratch_bytes(int V, int max_rows);
+// Rows of one sequence that form one attention work item (rows x query heads per kv head <= 64).
+int mfma_group_rows(const sdlm_model_cfg *m);
 
 // Repack rows of a row-major [N, K] bf16 matrix into tile order at row offset dst_row0 of a packed matrix with
 // dst_rows rows.  interleave: 0 plain; 1 / 2: the matrix is the gate / up half of the fused gate-up matrix,
 // whose 32-row tiles alternate gate, up.
 void launch_pack_mfma(hipStream_t s, void *dst, const void *src, int N, int K, int dst_row0, int dst_rows, int interleave);
-void launch_gemm_mfma(hipStream_t s, int epi, const GemmArgs &a);
-void launch_attn_mfma(hipStream_t s, const void *q, void *out, const void *pool_layer, const KvGeom &kg, const RowMeta &rm,
-                      const SeqState &st, int n_q_heads, int D, int max_rows, void *scratch);
-void launch_lmhead_mfma(hipStream_t s, const void *xhat, const void *w_packed, int max_rows, int V, int h, float scale,
-                        int conf_fn, float *logits_out, void *scratch, int32_t *ids, float *conf);
+// Returns the number of split-k slabs written to `slabs` for EPI_STORE_F32 (1: the result is in a.Yf); EPI_RESID
+// results are always complete in a.Yf on return.
+int launch_gemm_mfma(hipStream_t s, int epi, const GemmArgs &a, float *slabs, size_t slab_room_floats);
+void launch_attn_mfma(hipStream_t s, const sdlm_model_cfg *m, int max_seq_len, const void *q, void *out, const void *pool_layer,
+                      const KvGeom &kg, const RowMeta &rm, const SeqState &st, int D, int max_groups, void *scratch, size_t scratch_bytes);
+void launch_lmhead_mfma(hipStream_t s, const void *xhat, const void *w_packed, const int32_t *p_rows, int max_rows, int V, int h,
+                        float scale, int conf_fn, float *logits_out, void *scratch, int32_t *ids, float *conf);
 
 }  // namespace sdlm

@@ -24,7 +24,9 @@ struct Layout {
     size_t embed, lm_head, final_norm, rope, pool, state_i32, meta_i32;
     std::vector<size_t> layer_off;   // start of each layer's weights
     size_t l_attn_norm, l_wqkv, l_bqkv, l_wo, l_ffn_norm, l_gate, l_up, l_down, l_size;   // offsets inside a layer
-    size_t x, xn, qkv, q, att, act, xhat, logits, conf_rows, ids_rows, attn_part;
+    size_t x, xn, qkv, q, att, act, xhat, logits, conf_rows, ids_rows, attn_part, slabs, lm_part;
+    size_t slab_floats, attn_bytes;
+    int group_rows;
     size_t state_ints, meta_ints;
     int max_rows, max_groups, pages_per_seq, n_pages, pool_tiles, prefill_rows;
     size_t esz;
@@ -112,7 +114,12 @@ void plan(const sdlm_model_cfg *m, const sdlm_run_cfg *r, Layout *L)
     L->logits = take(L->mfma ? 256 : (size_t)B * D * V * 4);
     L->conf_rows = take((size_t)B * D * 4);
     L->ids_rows = take((size_t)B * D * 4);
-    L->attn_part = take(L->mfma ? mfma_attn_scratch_bytes(m, r, L->max_rows) : 256);
+    L->attn_bytes = L->mfma ? mfma_attn_scratch_bytes(m, r, L->max_rows) : 256;
+    L->attn_part = take(L->attn_bytes);
+    L->slab_floats = L->mfma ? ((size_t)8 << 20) : 64;                       // 32 MB of split-k slabs
+    L->slabs = take(L->slab_floats * 4);
+    L->lm_part = take(L->mfma ? mfma_lm_scratch_bytes(m->vocab, B * D) : 256);
+    L->group_rows = L->mfma ? mfma_group_rows(m) : GROUP_ROWS;
     L->total = o;
 }
 
@@ -135,7 +142,8 @@ struct sdlm_ctx {
     SeqState st;
     RowMeta rm;
     float *x, *qkv, *logits, *conf_rows;
-    void *xn, *q, *att, *act, *xhat, *attn_part;
+    void *xn, *q, *att, *act, *xhat, *attn_part, *lm_part;
+    float *slabs;
     int32_t *ids_rows;
     int batch = 0;
     bool prefilled = false, stepped = false;
@@ -200,7 +208,7 @@ void run_taps(sdlm_ctx *c, int layer, int which, const void *src, size_t bytes)
 
 // The decoder layers over the rows described by c->rm.  `rows` bounds the launch grids (the device-side row
 // count decides what is computed).
-void run_layers(sdlm_ctx *c, int rows)
+void run_layers(sdlm_ctx *c, int rows, int groups)
 {
     const sdlm_model_cfg &m = c->m;
     const int dt = m.dtype, h = m.hidden, F = m.ffn, d = m.head_dim;
@@ -213,35 +221,39 @@ void run_layers(sdlm_ctx *c, int rows)
         char *pool_l = c->pool + (size_t)l * c->kg.layer_stride * e;
         run_taps(c, l, 0, c->x, (size_t)rows * h * 4);
         { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xn, c->x, w.attn_norm, h, m.rms_eps, nullptr, c->rm.counts, rows); }
+        int qkv_slabs = 1;
         {
             Phase p(c, SDLM_PH_QKV);
             GemmArgs a{c->xn, w.wqkv, nullptr, m.has_qkv_bias ? w.bqkv : nullptr, c->qkv, nullptr, c->rm.counts, rows, nqkv, h, 1.f};
-            if (c->L.mfma) launch_gemm_mfma(s, EPI_STORE_F32, a); else launch_gemm_generic(s, dt, EPI_STORE_F32, a);
+            if (c->L.mfma) qkv_slabs = launch_gemm_mfma(s, EPI_STORE_F32, a, c->slabs, c->L.slab_floats); else launch_gemm_generic(s, dt, EPI_STORE_F32, a);
         }
-        { Phase p(c, SDLM_PH_ROPE); launch_rope_scatter(s, dt, c->qkv, c->q, pool_l, c->kg, c->rm, c->st, c->rope, m.n_q_heads, rows); }
+        {
+            Phase p(c, SDLM_PH_ROPE);
+            launch_rope_scatter(s, dt, qkv_slabs > 1 ? c->slabs : c->qkv, qkv_slabs, (size_t)rows * nqkv, c->q, pool_l, c->kg, c->rm, c->st, c->rope, m.n_q_heads, rows);
+        }
         run_taps(c, l, 5, c->q, (size_t)rows * nq * e);
         {
             Phase p(c, SDLM_PH_ATTN);
-            if (c->L.mfma) launch_attn_mfma(s, c->q, c->att, pool_l, c->kg, c->rm, c->st, m.n_q_heads, c->r.block_D, rows, c->attn_part);
+            if (c->L.mfma) launch_attn_mfma(s, &c->m, c->r.max_seq_len, c->q, c->att, pool_l, c->kg, c->rm, c->st, c->r.block_D, groups, c->attn_part, c->L.attn_bytes);
             else launch_attn_generic(s, dt, c->q, c->att, pool_l, c->kg, c->rm, c->st, m.n_q_heads, c->r.block_D, rows);
         }
         run_taps(c, l, 1, c->att, (size_t)rows * nq * e);
         {
             Phase p(c, SDLM_PH_OPROJ);
             GemmArgs a{c->att, w.wo, nullptr, nullptr, c->x, nullptr, c->rm.counts, rows, h, nq, 1.f};
-            if (c->L.mfma) launch_gemm_mfma(s, EPI_RESID, a); else launch_gemm_generic(s, dt, EPI_RESID, a);
+            if (c->L.mfma) launch_gemm_mfma(s, EPI_RESID, a, c->slabs, c->L.slab_floats); else launch_gemm_generic(s, dt, EPI_RESID, a);
         }
         { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xn, c->x, w.ffn_norm, h, m.rms_eps, nullptr, c->rm.counts, rows); }
         {
             Phase p(c, SDLM_PH_GATEUP);
             GemmArgs a{c->xn, w.w_gate, w.w_up, nullptr, nullptr, c->act, c->rm.counts, rows, F, h, 1.f};
-            if (c->L.mfma) launch_gemm_mfma(s, EPI_SWIGLU, a); else launch_gemm_generic(s, dt, EPI_SWIGLU, a);
+            if (c->L.mfma) launch_gemm_mfma(s, EPI_SWIGLU, a, c->slabs, c->L.slab_floats); else launch_gemm_generic(s, dt, EPI_SWIGLU, a);
         }
         run_taps(c, l, 2, c->act, (size_t)rows * F * e);
         {
             Phase p(c, SDLM_PH_DOWN);
             GemmArgs a{c->act, w.w_down, nullptr, nullptr, c->x, nullptr, c->rm.counts, rows, h, F, 1.f};
-            if (c->L.mfma) launch_gemm_mfma(s, EPI_RESID, a); else launch_gemm_generic(s, dt, EPI_RESID, a);
+            if (c->L.mfma) launch_gemm_mfma(s, EPI_RESID, a, c->slabs, c->L.slab_floats); else launch_gemm_generic(s, dt, EPI_RESID, a);
         }
         run_taps(c, l, 3, c->x, (size_t)rows * h * 4);
     }
@@ -316,7 +328,7 @@ int sdlm_create(const sdlm_model_cfg *m, const sdlm_run_cfg *r, void *workspace,
     c->x = (float *)(ws + L.x); c->xn = ws + L.xn; c->qkv = (float *)(ws + L.qkv); c->q = ws + L.q; c->att = ws + L.att;
     c->act = ws + L.act; c->xhat = ws + L.xhat; c->logits = (float *)(ws + L.logits);
     c->conf_rows = (float *)(ws + L.conf_rows); c->ids_rows = (int32_t *)(ws + L.ids_rows);
-    c->attn_part = ws + L.attn_part;
+    c->attn_part = ws + L.attn_part; c->slabs = (float *)(ws + L.slabs); c->lm_part = ws + L.lm_part;
     c->n_ub.assign(B, 0);
     c->info = L.mfma ? "mfma-bf16" : (m->dtype == 0 ? "generic-fp32" : "generic-bf16");
     // rotary table: (cos, sin)(pos * theta^(-2i/d)), evaluated in double on the host
@@ -447,9 +459,9 @@ int sdlm_prefill(sdlm_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
     auto flush = [&]() -> int {
         if (tok.empty()) return SDLM_OK;
         int R = (int)tok.size();
-        for (int r0 = 0; r0 < R;) {   // groups: runs of <= GROUP_ROWS rows of one sequence
+        for (int r0 = 0; r0 < R;) {   // groups: runs of <= group_rows rows of one sequence
             int r1 = r0 + 1;
-            while (r1 < R && r1 - r0 < GROUP_ROWS && seq[r1] == seq[r0]) ++r1;
+            while (r1 < R && r1 - r0 < c->L.group_rows && seq[r1] == seq[r0]) ++r1;
             g0.push_back(r0); gn.push_back(r1 - r0); gs.push_back(seq[r0]);
             r0 = r1;
         }
@@ -463,7 +475,7 @@ int sdlm_prefill(sdlm_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
         HIPCHK(c, hipMemcpyAsync(c->rm.grp_n, gn.data(), gn.size() * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.grp_seq, gs.data(), gs.size() * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.counts, counts, sizeof counts, hipMemcpyHostToDevice, s));
-        run_layers(c, R);
+        run_layers(c, R, (int)g0.size());
         HIPCHK(c, hipStreamSynchronize(s));   // the host vectors are reused
         tok.clear(); pos.clear(); seq.clear(); kind.clear(); lim.clear(); g0.clear(); gn.clear(); gs.clear();
         return SDLM_OK;
@@ -498,15 +510,15 @@ int sdlm_decode_step(sdlm_ctx *c, int32_t *ids, int32_t *count, float *conf, flo
     }
     hipStream_t s = c->stream;
     const int rows = B * 2 * D;
-    { Phase p(c, SDLM_PH_ROWS); launch_assemble_decode(s, c->st, c->rm, B, D, c->m.mask_token_id); }
-    run_layers(c, rows);
+    { Phase p(c, SDLM_PH_ROWS); launch_assemble_decode(s, c->st, c->rm, B, D, c->m.mask_token_id, c->L.group_rows); }
+    run_layers(c, rows, B * ((2 * D + c->L.group_rows - 1) / c->L.group_rows));
     const int dt = c->m.dtype, h = c->m.hidden, V = c->m.vocab;
     { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xhat, c->x, c->final_norm, h, c->m.rms_eps, c->rm.blk_row, c->rm.counts + 2, B * D); }
     run_taps(c, 0, 4, c->xhat, (size_t)B * D * h * c->L.esz);
     {
         Phase p(c, SDLM_PH_LMHEAD);
         if (c->L.mfma) {
-            launch_lmhead_mfma(s, c->xhat, c->lm_head, B * D, V, h, c->m.logit_scale, c->r.conf_fn, logits, c->attn_part,
+            launch_lmhead_mfma(s, c->xhat, c->lm_head, c->rm.counts + 2, B * D, V, h, c->m.logit_scale, c->r.conf_fn, logits, c->lm_part,
                                c->ids_rows, c->conf_rows);
         } else {
             float *z = logits ? logits : c->logits;

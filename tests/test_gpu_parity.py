@@ -37,7 +37,7 @@ def test_c1_tiny_fp32_free_running():
     ctx.close()
 
 
-@pytest.mark.parametrize("D,tau,paged", [(1, 0.5, False), (2, 0.2, True), (4, 0.05, False), (4, 0.05, True), (8, 0.02, True), (16, 0.01, False)])
+@pytest.mark.parametrize("D,tau,paged", [(1, 0.5, False), (2, 0.9, True), (4, 0.8, False), (4, 0.8, True), (8, 0.6, True), (16, 0.3, False)])
 def test_small_fp32_ragged_batch(D, tau, paged):
     """Ragged batch, several block sizes, both cache layouts, override and own commits alternating."""
     m = gpu_cfg()
@@ -72,7 +72,7 @@ def test_confidence_and_rule_variants(conf_fn, rule):
 def test_small_bf16_generic_kernels():
     """bf16 storage through the shape-generic kernels (head_dim 64 is not served by the matrix-core path)."""
     m = gpu_cfg(dtype="bf16", head_dim=64, hidden=128, n_q_heads=4, n_kv_heads=2)
-    om, g_dev, layers_dev = both_models(m, seed=7, std=0.3)
+    om, g_dev, layers_dev = both_models(m, seed=7, std=0.08)
     prompts = [syn.uniform_int(4, f"b{i}", n, 0, m.vocab - 1).numpy() for i, n in enumerate([3, 20, 37])]
     ctx = gpu_context(m, g_dev, layers_dev, max_batch=3, max_seq_len=80, D=4, tau=0.1, paged=True, n_pages=20)
     st, _ = lockstep(ctx, om, prompts, 4, 0.1, 6, logit_tol=2e-2, conf_tol=2e-2, bf16=True)
@@ -191,3 +191,46 @@ def test_generator_is_identical_on_cpu_and_gpu():
     b = syn.normal(3, "dev", (1000, 33), 0.02, torch.bfloat16, "cuda")
     assert torch.equal(a, b.cpu())
     assert torch.equal(syn.uniform_int(3, "u", 5000, 0, 151935), syn.uniform_int(3, "u", 5000, 0, 151935, device="cuda").cpu())
+
+
+# ------------------------------------------------------------------ bf16 matrix-core path (head_dim 128)
+
+def mfma_cfg(**kw):
+    base = dict(n_layers=2, hidden=256, n_q_heads=4, n_kv_heads=2, head_dim=128, ffn=512, vocab=2048, dtype="bf16",
+                rope_theta=1.0e6, has_qkv_bias=True)
+    base.update(kw)
+    return syn.ModelCfg(**base)
+
+
+@pytest.mark.parametrize("name,kw,lens,D,tau,paged", [
+    ("g2", {}, [1, 9, 40, 100], 4, 0.6, True),
+    ("g7-ragged-vocab", dict(n_q_heads=14, n_kv_heads=2, vocab=1000, ffn=320), [3, 17, 33, 64, 70], 4, 0.6, True),
+    ("g8-D8-two-groups", dict(n_q_heads=16, n_kv_heads=2, hidden=512), [5, 130, 300], 8, 0.5, False),
+    ("g6-D4-batch1-long", dict(n_q_heads=12, n_kv_heads=2, hidden=384, ffn=1024), [700], 4, 0.6, False),
+    ("g5-D16", dict(n_q_heads=10, n_kv_heads=2, hidden=320, ffn=640, has_qkv_bias=False), [2, 50], 16, 0.3, True),
+])
+def test_bf16_mfma_path(name, kw, lens, D, tau, paged):
+    """The bf16 product path: MFMA GEMMs, MFMA block-masked attention (split KV), fused LM-head reduction."""
+    m = mfma_cfg(**kw)
+    om, g_dev, layers_dev = both_models(m, seed=21, std=0.05)
+    prompts = [syn.uniform_int(D, f"{name}{i}", n, 0, m.vocab - 1).numpy() for i, n in enumerate(lens)]
+    steps = 6
+    ovr = syn.make_overrides(13, steps, len(lens), D, m.vocab)
+    max_len = max(lens) + steps * D + D
+    n_pages = sum((n + steps * D + 15) // 16 + 1 for n in lens)
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=len(lens), max_seq_len=max_len, D=D, tau=tau, paged=paged, n_pages=n_pages,
+                      prefill_rows=128)
+    assert ctx.kernel_info == "mfma-bf16"
+    st, _ = lockstep(ctx, om, prompts, D, tau, steps, logit_tol=2e-2, conf_tol=1e-3, overrides=ovr, bf16=True, max_len=max_len)
+    print(name, st)
+    ctx.close()
+
+
+def test_bf16_mfma_entropy_confidence():
+    m = mfma_cfg()
+    om, g_dev, layers_dev = both_models(m, seed=22, std=0.05)
+    prompts = [syn.uniform_int(1, f"e{i}", n, 0, m.vocab - 1).numpy() for i, n in enumerate([12, 31])]
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=2, max_seq_len=80, D=4, tau=0.05, conf_fn=1)
+    st, _ = lockstep(ctx, om, prompts, 4, 0.05, 4, logit_tol=2e-2, conf_tol=1e-3, conf_fn=1, bf16=True)
+    print(st)
+    ctx.close()
