@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the SDLM block-decode step on one MI355X.
+
+A "step" is one pass of the whole hot path over the batch: row assembly, embedding, L decoder layers (RMSNorm,
+QKV GEMM, RoPE + K/V placement, block-masked attention, O projection, gate/up GEMM + SwiGLU, down projection),
+final norm, LM head with fused online softmax / arg-max, prefix acceptance, and the commit that publishes the
+accepted tokens.  Inputs (weights, prompts) are synthetic and already resident in HBM when the clock starts.
+
+Prints ONE JSON line: metric = accepted tokens/s over the timed steps, plus block-step latency, the roofline
+object of the dominant kernel (HIP-event timed inside the timed region) and the CPU oracle baseline.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
+PEAK_BF16_TFLOPS = 2500.0    # dense MFMA bf16
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=512)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--config", default="C4", help="C1..C5 (default: the 7B-shaped workload the target is quoted on)")
+    ap.add_argument("--tau", type=float, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true", help="also time the other thresholds of the workload's tau sweep")
+    ap.add_argument("--profile-all", action="store_true", help="bracket every phase with events (adds overhead)")
+    return ap.parse_args()
+
+
+def build_model(ctx, m, seed, keep_host_layers=None):
+    """Generate weights on the GPU layer by layer and hand them to the library; optionally keep host copies."""
+    import torch
+    from paper_2509_24007_amd import inputs as syn
+    g = syn.make_globals(m, seed, device="cuda")
+    ctx.init_weights(g, None)
+    host_g = {k: v.cpu() for k, v in g.items()} if keep_host_layers is not None else None
+    torch.cuda.synchronize()
+    del g
+    host_layers = []
+    for l in range(m.n_layers):
+        L = syn.make_layer(m, seed, l, device="cuda")
+        ctx.init_weights(None, {l: L})
+        if keep_host_layers is not None and l < keep_host_layers:
+            host_layers.append({k: (v.cpu() if v is not None else None) for k, v in L.items()})
+        torch.cuda.synchronize()
+        del L
+    torch.cuda.empty_cache()
+    return host_g, host_layers
+
+
+def algorithmic_bytes(m, esz, lens_sum, R):
+    """Bytes one step must move: every weight once, every cached K/V once, plus the small activations."""
+    d, h, F, V = m.head_dim, m.hidden, m.ffn, m.vocab
+    nq, nk = m.n_q_heads * d, m.n_kv_heads * d
+    per_layer = (nq + 2 * nk) * h + h * nq + 3 * F * h
+    weights = (per_layer * m.n_layers + V * h) * esz
+    kv = lens_sum * 2 * nk * esz * m.n_layers
+    return weights, kv
+
+
+def run_tau(ctx, m, r, prompts, tau_idx, steps, warmup, prof_phases):
+    import torch
+    B, D = len(prompts), r.block_D
+    ctx.prefill(prompts)
+    torch.cuda.synchronize()
+    ids = torch.zeros(warmup + steps, B, D, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(warmup + steps, B, dtype=torch.int32, device="cuda")
+    for t in range(warmup):
+        ctx.decode_step(ids[t], cnt[t])
+        ctx.kv_commit()
+    torch.cuda.synchronize()
+    ctx.profile(prof_phases)
+    t0 = time.perf_counter()
+    for t in range(warmup, warmup + steps):
+        ctx.decode_step(ids[t], cnt[t])
+        ctx.kv_commit()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    phases = ctx.profile_read()
+    ctx.profile(None)
+    n, c = ctx.get_lengths()
+    return t1 - t0, cnt.cpu(), phases, n
+
+
+def cpu_baseline(m, host_g, host_layers, prompt, D, tau, n_steps=2, prompt_tokens=8):
+    from oracle import oracle as orc
+    om = orc.model_from_inputs(m, host_g, host_layers)
+    seq = orc.Seq(om, prompt_tokens + n_steps * D + D)
+    t0 = time.perf_counter()
+    seq.prefill(prompt[:prompt_tokens])
+    t_pre = time.perf_counter() - t0
+    acc, t_steps = 0, 0.0
+    for _ in range(n_steps):
+        t0 = time.perf_counter()
+        _, _, _, g = seq.step(D, tau, want_logits=False)
+        seq.commit()
+        t_steps += time.perf_counter() - t0
+        acc += g
+    return {"value": acc / t_steps, "unit": "accepted tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"sequence 0 truncated to its first {prompt_tokens} prompt tokens, {n_steps} decode steps, all "
+                      f"{m.n_layers} layers and the full vocabulary; the oracle decodes one sequence at a time, so its rate "
+                      f"does not grow with the batch (prefill of the sample took {t_pre:.1f} s, not counted)",
+            "ms_per_step_per_sequence": 1e3 * t_steps / n_steps}
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        print("bench.py: this build measures the block-decode step on ONE GPU; --gpus %d is not supported "
+              "(the path shards by sequences, see DESIGN.md)" % a.gpus, file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2509_24007_amd import inputs as syn
+    from paper_2509_24007_amd import sdlm
+
+    wl = syn.workloads()[a.config]
+    m, r = wl.model, wl.run
+    tau = a.tau if a.tau is not None else r.tau
+    taus = [tau] + ([t for t in (r.taus or []) if t != tau] if a.sweep else [])
+    B, D = r.batch, r.block_D
+    prompts = [p.numpy() for p in syn.make_prompts(wl.seed, B, r.prompt_lo, r.prompt_hi, m.vocab)]
+    total_steps = a.warmup + a.steps
+    max_len = max(len(p) for p in prompts) + total_steps * D + D
+    n_pages = sum((len(p) + total_steps * D + D + 15) // 16 + 1 for p in prompts) if r.paged else 0
+    ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=B, max_seq_len=max_len, block_D=D, tau=tau, paged=r.paged,
+                       n_pages=n_pages)
+    want_cpu = not a.no_cpu_baseline
+    t0 = time.perf_counter()
+    host_g, host_layers = build_model(ctx, m, wl.seed, keep_host_layers=m.n_layers if want_cpu else None)
+    t_build = time.perf_counter() - t0
+    prof = True if a.profile_all else ("attn", "qkv", "oproj", "gateup", "down", "lmhead")
+    esz = 4 if m.dtype == "fp32" else 2
+    results = []
+    for ti, tv in enumerate(taus):
+        if ti > 0:
+            ctx.close()
+            ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=B, max_seq_len=max_len, block_D=D, tau=tv, paged=r.paged, n_pages=n_pages)
+            build_model(ctx, m, wl.seed)
+        t0 = time.perf_counter()
+        dt, cnt, phases, n_end = run_tau(ctx, m, r, prompts, ti, a.steps, a.warmup, prof)
+        t_total = time.perf_counter() - t0
+        timed = cnt[a.warmup:].numpy().astype(np.int64)
+        accepted = int(timed.sum())
+        hist = np.bincount(timed.ravel(), minlength=D + 1)[1:].tolist()
+        # context length of every sequence at every timed step (prompt + everything accepted before the step)
+        lens0 = np.array([len(p) for p in prompts], dtype=np.int64)
+        before = lens0[None, :] + np.concatenate([np.zeros((1, B), np.int64), np.cumsum(cnt.numpy().astype(np.int64), 0)[:-1]], 0)
+        ctx_timed = before[a.warmup:]
+        pend = np.concatenate([np.zeros((1, B), np.int64), cnt.numpy().astype(np.int64)[:-1]], 0)[a.warmup:]
+        R_mean = float((pend + D).sum(1).mean())
+        w_bytes, kv_bytes = algorithmic_bytes(m, esz, float(ctx_timed.sum(1).mean()), R_mean)
+        results.append(dict(tau=tv, dt=dt, accepted=accepted, hist=hist, phases=phases, R_mean=R_mean,
+                            w_bytes=w_bytes, kv_bytes=kv_bytes, ctx_mean=float(ctx_timed.mean()), t_total=t_total))
+    main_r = results[0]
+    ms_per_step = 1e3 * main_r["dt"] / a.steps
+    # per-kernel accounting (per launch = one layer's kernel, or the LM head)
+    d, h, F, V, L = m.head_dim, m.hidden, m.ffn, m.vocab, m.n_layers
+    nq, nk = m.n_q_heads * d, m.n_kv_heads * d
+    Rm = main_r["R_mean"]
+    kv_layer = main_r["kv_bytes"] / L
+    kern = {
+        "attn": dict(bytes=kv_layer + 2 * Rm * nq * esz, flops=0.0),
+        "qkv": dict(bytes=(nq + 2 * nk) * h * esz, flops=2.0 * Rm * (nq + 2 * nk) * h),
+        "oproj": dict(bytes=h * nq * esz, flops=2.0 * Rm * h * nq),
+        "gateup": dict(bytes=2 * F * h * esz, flops=4.0 * Rm * F * h),
+        "down": dict(bytes=F * h * esz, flops=2.0 * Rm * F * h),
+        "lmhead": dict(bytes=V * h * esz, flops=2.0 * B * D * V * h),
+    }
+    # attention flops: 4 * d per (query row, head, visible key); rows of a sequence see about its context
+    kern["attn"]["flops"] = 4.0 * d * m.n_q_heads * float(((main_r["ctx_mean"]) * Rm))
+    table = {}
+    for name, k in kern.items():
+        ms, launches = main_r["phases"].get(name, (0.0, 0))
+        if launches == 0:
+            continue
+        avg = ms / launches
+        t_hbm = k["bytes"] / (PEAK_HBM_GBS * 1e9)
+        t_mfma = k["flops"] / (PEAK_BF16_TFLOPS * 1e12)
+        table[name] = dict(ms_total=ms, launches=launches, avg_us=1e3 * avg, gbs=k["bytes"] / (avg * 1e-3) / 1e9,
+                           tflops=k["flops"] / (avg * 1e-3) / 1e12, bound="hbm" if t_hbm >= t_mfma or m.dtype == "fp32" else "mfma")
+    roof = None
+    if table:
+        dom = max(table, key=lambda k: table[k]["ms_total"])
+        t = table[dom]
+        if t["bound"] == "hbm":
+            roof = dict(kernel=dom, bound="hbm", achieved=t["gbs"], peak=PEAK_HBM_GBS, unit="GB/s", frac=t["gbs"] / PEAK_HBM_GBS, traffic=None)
+        else:
+            roof = dict(kernel=dom, bound="mfma", achieved=t["tflops"], peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
+                        frac=t["tflops"] / PEAK_BF16_TFLOPS, traffic=None)
+        roof["avg_launch_us"] = t["avg_us"]
+        roof["launches"] = t["launches"]
+    step_bytes = main_r["w_bytes"] + main_r["kv_bytes"]
+    out = {
+        "metric": "accepted tokens/sec and block-step latency; achieved HBM GB/s vs peak",
+        "value": main_r["accepted"] / main_r["dt"],
+        "unit": "accepted tokens/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if m.dtype == "fp32" else "bf16",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "batch": B, "block_D": D, "tau": main_r["tau"], "paged_kv": bool(r.paged),
+                   "prompt_len": [r.prompt_lo, r.prompt_hi], "kernels": ctx.kernel_info},
+        "gamma_hist": main_r["hist"],
+        "tokens_per_step_per_seq": main_r["accepted"] / (a.steps * B),
+        "rows_per_step": main_r["R_mean"],
+        "mean_context": main_r["ctx_mean"],
+        "step_algorithmic_GB": step_bytes / 1e9,
+        "step_hbm_GBs": step_bytes / (ms_per_step * 1e-3) / 1e9,
+        "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "roofline": roof,
+        "kernels": {k: {kk: (round(vv, 3) if isinstance(vv, float) else vv) for kk, vv in v.items()} for k, v in table.items()},
+        "setup_s": {"weights": round(t_build, 1), "prefill_and_run": round(main_r["t_total"], 1)},
+    }
+    if len(results) > 1:
+        out["tau_sweep"] = [dict(tau=x["tau"], value=x["accepted"] / x["dt"], ms_per_step=1e3 * x["dt"] / a.steps,
+                                 gamma_hist=x["hist"]) for x in results]
+    ctx.close()
+    del ctx
+    torch.cuda.empty_cache()
+    if want_cpu:
+        steps_cpu = 2 if m.n_layers * m.hidden > 20000 else 8
+        out["cpu_baseline"] = cpu_baseline(m, host_g, host_layers, prompts[0], D, tau, n_steps=steps_cpu,
+                                           prompt_tokens=min(8, len(prompts[0])))
+    else:
+        out["cpu_baseline"] = None
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

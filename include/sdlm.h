@@ -183,13 +183,14 @@ int sdlm_debug_read_kv(sdlm_ctx *ctx, int32_t layer, int32_t seq, int32_t kv_hea
 int32_t sdlm_max_rows(const sdlm_ctx *ctx);
 
 /*
- * Per-phase GPU time.  sdlm_profile(ctx, 1) makes every later step bracket its phases with HIP events on the
- * context's stream; sdlm_profile_read synchronises, adds up the events recorded since the last read and
+ * Per-phase GPU time.  sdlm_profile(ctx, mask) makes every later step bracket each phase p whose bit (1 << p) is
+ * set in `mask` with HIP events on the context's stream (-1: all phases, 0: none); sdlm_profile_read
+ * synchronises, adds up the events recorded since the last read and
  * returns, for phase p in 0..SDLM_N_PHASES-1, total milliseconds in ms[p] and launches in launches[p] ([host]).
  */
 enum { SDLM_PH_ROWS = 0, SDLM_PH_NORM, SDLM_PH_QKV, SDLM_PH_ROPE, SDLM_PH_ATTN, SDLM_PH_OPROJ, SDLM_PH_GATEUP,
        SDLM_PH_DOWN, SDLM_PH_LMHEAD, SDLM_PH_ACCEPT, SDLM_N_PHASES };
-int sdlm_profile(sdlm_ctx *ctx, int32_t enable);
+int sdlm_profile(sdlm_ctx *ctx, int32_t mask);
 int sdlm_profile_read(sdlm_ctx *ctx, float *ms, int32_t *launches);
 
 /* Which kernel family serves the GEMMs and the attention: "generic-fp32", "mfma-bf16", ... ([host] string). */

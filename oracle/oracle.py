@@ -50,6 +50,8 @@ def lib():
         build()
         L = C.CDLL(_LIB)
         i32, f32, f64, vp = C.c_int32, C.c_float, C.c_double, C.c_void_p
+        L.orc_num_threads.restype = i32
+        L.orc_num_threads.argtypes = []
         L.orc_argmax.restype = i32
         L.orc_argmax.argtypes = [vp, i32]
         L.orc_conf_logit.restype = f64
@@ -175,6 +177,10 @@ def model_from_inputs(mcfg, globals_, layers) -> Model:
 
 def _i32(a) -> np.ndarray:
     return np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+
+
+def num_threads() -> int:
+    return int(lib().orc_num_threads())
 
 
 # ------------------------------------------------------------------ scalar rules

@@ -45,6 +45,9 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 typedef struct {
     int32_t n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab;
@@ -59,6 +62,16 @@ typedef struct {
     const void *const *bq, *const *bk, *const *bv;    /* entries may be NULL */
     const void *const *ffn_norm, *const *w_gate, *const *w_up, *const *w_down;
 } orc_weights;
+
+/* Threads the OpenMP loops use (for reporting only). */
+int32_t orc_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 /* ---------------------------------------------------------------- helpers */
 

@@ -20,6 +20,7 @@ namespace sdlm {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int XS_STRIDE = 72;   // bf16 elements per LDS row of the activation slice (64 + 8 padding)
 
@@ -111,48 +112,58 @@ __global__ __launch_bounds__(256) void gemm_mfma_k(MfmaArgs a)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[nt][mt][v] = 0.f;
 
-    bf16x8 wc[NT][4], wn[NT][4];
-    uint4 xr[MT];
+    // Software pipeline: the weight operands of slice s+2 and the activation slice s+1 are requested at the top of
+    // slice s.  Three rotating register sets hold the weights (the loop is unrolled by three so that the sets keep
+    // static names); the activations go registers -> LDS at the bottom of the slice.  Activation loads are issued
+    // before the weight loads: the counter that orders returns is in program order, so waiting for the (L2-hot)
+    // activations leaves the (HBM) weight loads in flight.
+    bf16x8 w0[NT][4], w1[NT][4], w2[NT][4];
+    u32x4 xr[MT];
+    const int s_last = s_end - 1;
+#define SDLM_LOAD_W(dst, stage)                                                                                   \
+    {                                                                                                             \
+        const size_t so_ = (size_t)min((stage), s_last) * 4 * 512;                                                \
+        _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                        \
+            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) dst[nt][ks] = *(const bf16x8 *)(wp[nt] + so_ + ks * 512); \
+    }
+#define SDLM_LOAD_X(stage)                                                                                        \
+    {                                                                                                             \
+        const size_t xo_ = (size_t)min((stage), s_last) * 64;                                                     \
+        _Pragma("unroll") for (int i = 0; i < MT; ++i) xr[i] = *(const u32x4 *)(xp[i] + xo_);                    \
+    }
+    SDLM_LOAD_X(s_begin);
+    SDLM_LOAD_W(w0, s_begin);
+    SDLM_LOAD_W(w1, s_begin + 1);
 #pragma unroll
-    for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) wc[nt][ks] = *(const bf16x8 *)(wp[nt] + ((size_t)s_begin * 4 + ks) * 512);
-#pragma unroll
-    for (int i = 0; i < MT; ++i) xr[i] = *(const uint4 *)(xp[i] + (size_t)s_begin * 64);
-#pragma unroll
-    for (int i = 0; i < MT; ++i) *(uint4 *)&Xs[0][i * 32 + xrow][xchunk * 8] = xr[i];
+    for (int i = 0; i < MT; ++i) *(u32x4 *)&Xs[0][i * 32 + xrow][xchunk * 8] = xr[i];
     __syncthreads();
 
     const int brow = lane & 31, bk = (lane >> 5) * 8;
-    for (int s = s_begin; s < s_end; ++s) {
-        const int buf = (s - s_begin) & 1;
-        const bool more = s + 1 < s_end;
-        if (more) {
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) wn[nt][ks] = *(const bf16x8 *)(wp[nt] + ((size_t)(s + 1) * 4 + ks) * 512);
-#pragma unroll
-            for (int i = 0; i < MT; ++i) xr[i] = *(const uint4 *)(xp[i] + (size_t)(s + 1) * 64);
-        }
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks)
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                bf16x8 b = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][ks * 16 + bk];
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wc[nt][ks], b, acc[nt][mt], 0, 0, 0);
-            }
-        if (more) {
-#pragma unroll
-            for (int i = 0; i < MT; ++i) *(uint4 *)&Xs[buf ^ 1][i * 32 + xrow][xchunk * 8] = xr[i];
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) wc[nt][ks] = wn[nt][ks];
-        }
-        __syncthreads();
+    int buf = 0;
+#define SDLM_STAGE(WC, WN, stage)                                                                                 \
+    if ((stage) < s_end) {                                                                                        \
+        SDLM_LOAD_X((stage) + 1);                                                                                 \
+        SDLM_LOAD_W(WN, (stage) + 2);                                                                             \
+        __builtin_amdgcn_sched_barrier(0);                                                                        \
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                                         \
+            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                                  \
+                bf16x8 b_ = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][ks * 16 + bk];                              \
+                _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                \
+                    acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WC[nt][ks], b_, acc[nt][mt], 0, 0, 0);  \
+            }                                                                                                     \
+        __builtin_amdgcn_sched_barrier(0);                                                                        \
+        _Pragma("unroll") for (int i = 0; i < MT; ++i) *(u32x4 *)&Xs[buf ^ 1][i * 32 + xrow][xchunk * 8] = xr[i]; \
+        buf ^= 1;                                                                                                 \
+        __syncthreads();                                                                                          \
     }
+    for (int s = s_begin; s < s_end; s += 3) {
+        SDLM_STAGE(w0, w2, s)
+        SDLM_STAGE(w1, w0, s + 1)
+        SDLM_STAGE(w2, w1, s + 2)
+    }
+#undef SDLM_STAGE
+#undef SDLM_LOAD_W
+#undef SDLM_LOAD_X
 
     // accumulator element v of lane l: output feature 8*(v/4) + 4*(l/32) + v%4 of the tile, activation row l%32
     const int fbase = (lane >> 5) * 4;

@@ -150,7 +150,7 @@ struct sdlm_ctx {
     std::vector<int32_t> n_ub;           // host upper bound of n_b
     std::vector<Tap> taps;
     // profiling
-    bool prof = false;
+    uint32_t prof = 0;                   // bit p: phase p is bracketed by events
     std::vector<hipEvent_t> ev;          // pairs
     std::vector<int> ev_phase;
     size_t ev_used = 0;
@@ -181,7 +181,7 @@ struct Phase {
     size_t idx = (size_t)-1;
     Phase(sdlm_ctx *c_, int ph) : c(c_)
     {
-        if (!c->prof) return;
+        if (!((c->prof >> ph) & 1u)) return;
         if (c->ev_used + 2 > c->ev.size()) {
             hipEvent_t a, b;
             if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
@@ -616,7 +616,7 @@ int32_t sdlm_max_rows(const sdlm_ctx *c) { return c ? c->L.max_rows : 0; }
 int sdlm_profile(sdlm_ctx *c, int32_t enable)
 {
     if (!c) return SDLM_EINVAL;
-    c->prof = enable != 0;
+    c->prof = (uint32_t)enable;
     return SDLM_OK;
 }
 

@@ -259,8 +259,17 @@ class Context:
         torch.cuda.synchronize(self.device)
         return k.cpu(), v.cpu()
 
-    def profile(self, enable: bool) -> None:
-        self._check(self.L.sdlm_profile(self.h, 1 if enable else 0))
+    def profile(self, phases=None) -> None:
+        """phases: None/False -> off, True -> all, or an iterable of phase names to bracket with events."""
+        if phases is None or phases is False:
+            mask = 0
+        elif phases is True:
+            mask = -1
+        else:
+            mask = 0
+            for p in phases:
+                mask |= 1 << PHASES.index(p)
+        self._check(self.L.sdlm_profile(self.h, mask))
 
     def profile_read(self):
         ms = (C.c_float * len(PHASES))()
