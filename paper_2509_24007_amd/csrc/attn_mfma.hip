@@ -21,6 +21,7 @@ typedef __attribute__((ext_vector_type(4))) float f32x4;
 constexpr int NQ = 4;     // 16-query tiles per work item
 constexpr int QMAX = NQ * 16;
 constexpr int HD = 128;
+constexpr float RESCALE_GAP = 8.0f;   // log2 units
 
 struct AttnArgs {
     const bf16_t *q;
@@ -34,11 +35,6 @@ struct AttnArgs {
     float2 *part_ml;    // [item][QMAX]
     float c;            // log2(e) / sqrt(d)
 };
-
-__device__ inline uint32_t pack_bf16(float lo, float hi)
-{
-    return (uint32_t)f_to_bf16(lo) | ((uint32_t)f_to_bf16(hi) << 16);
-}
 
 union Op8 { bf16x8 v; uint4 u; uint2 h[2]; uint32_t w[4]; };
 
@@ -97,50 +93,52 @@ __global__ __launch_bounds__(256) void attn_mfma_k(AttnArgs a)
     const int32_t *ptab = a.st.page_table + (size_t)b * a.kg.pages_per_seq;
     const size_t tile_elems = 2 * PAGE * HD;
     const int n_pairs = (nv + 1) / 2;
-    for (int pp = wave; pp < n_pairs; pp += 4) {
-        // the two virtual tiles of this pair; an absent second tile aliases the first and is masked out
-        int uA = 2 * pp, uB = 2 * pp + 1;
-        bool hasB = uB < nv;
-        bool stgA = uA >= n_cache, stgB = hasB && uB >= n_cache;
-        int pgA = stgA ? a.kg.staging_base + b : ptab[c0 + uA];
-        int pgB = !hasB ? pgA : (stgB ? a.kg.staging_base + b : ptab[c0 + uB]);
+    const int stg_page = a.kg.staging_base + b;
+
+    // One pair of tiles (32 keys): K operands of both tiles, V^T operands with the two tiles side by side.
+    struct Pair { Op8 kA[4], kB[4], v[8]; };
+    // Request pair pp: 16 KB per wavefront, global -> registers.  An absent second tile aliases the first.
+    auto load_pair = [&](Pair &t, int pp) {
+        const int uA = 2 * pp, uB = 2 * pp + 1;
+        const bool hasB = uB < nv;
+        const int pgA = uA >= n_cache ? stg_page : ptab[c0 + uA];
+        const int pgB = !hasB ? pgA : (uB >= n_cache ? stg_page : ptab[c0 + uB]);
         const bf16_t *tA = a.pool + ((size_t)pgA * a.kg.n_kv_heads + hk) * tile_elems;
         const bf16_t *tB = a.pool + ((size_t)pgB * a.kg.n_kv_heads + hk) * tile_elems;
-        Op8 kA[4], kB[4];
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            kA[kk].u = *(const uint4 *)(tA + (kk * 64 + lane) * 8);
-            kB[kk].u = *(const uint4 *)(tB + (kk * 64 + lane) * 8);
+            t.kA[kk].u = *(const uint4 *)(tA + (kk * 64 + lane) * 8);
+            t.kB[kk].u = *(const uint4 *)(tB + (kk * 64 + lane) * 8);
         }
-        Op8 vop[8];
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) {
-            vop[dt].h[0] = *(const uint2 *)(tA + PAGE * HD + (dt * 64 + lane) * 4);
-            vop[dt].h[1] = *(const uint2 *)(tB + PAGE * HD + (dt * 64 + lane) * 4);
+            t.v[dt].h[0] = *(const uint2 *)(tA + PAGE * HD + (dt * 64 + lane) * 4);
+            t.v[dt].h[1] = *(const uint2 *)(tB + PAGE * HD + (dt * 64 + lane) * 4);
         }
-        // scores: lane (query n, group lg) gets keys 4 lg .. 4 lg + 3 of each tile
-        f32x4 sA[NQ], sB[NQ];
-#pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) {
-            sA[nq] = f32x4{0.f, 0.f, 0.f, 0.f};
-            sB[nq] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int kk = 0; kk < 4; ++kk) {
-                sA[nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kA[kk].v, qop[nq][kk].v, sA[nq], 0, 0, 0);
-                sB[nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kB[kk].v, qop[nq][kk].v, sB[nq], 0, 0, 0);
-            }
-        }
+    };
+    // Scores, mask, online softmax and P V for one pair, one 16-query tile at a time.
+    auto compute_pair = [&](Pair &t, int pp) {
+        const int uA = 2 * pp, uB = 2 * pp + 1;
+        const bool hasB = uB < nv;
+        const bool stgA = uA >= n_cache, stgB = hasB && uB >= n_cache;
         const int keyA = (c0 + uA) * PAGE + lg * 4, keyB = (c0 + uB) * PAGE + lg * 4;
         const bool fullA = !stgA && (c0 + uA + 1) * PAGE <= min_lim;
         const bool fullB = hasB && !stgB && (c0 + uB + 1) * PAGE <= min_lim;
-        bool changed = false;
-        float m_new[NQ];
 #pragma unroll
         for (int nq = 0; nq < NQ; ++nq) {
+            if (nq * 16 >= QR) continue;
+            // lane (query n, group lg) gets keys 4 lg .. 4 lg + 3 of each tile
+            f32x4 sA = {0.f, 0.f, 0.f, 0.f}, sB = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) {
+                sA = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.kA[kk].v, qop[nq][kk].v, sA, 0, 0, 0);
+                sB = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.kB[kk].v, qop[nq][kk].v, sB, 0, 0, 0);
+            }
+            // raw scores; the softmax scale is folded into the exponent: p = 2^(c s - c m)
             float mx = -INFINITY;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
-                float x = sA[nq][v] * a.c, y = sB[nq][v] * a.c;
+                float x = sA[v], y = sB[v];
                 if (!fullA) {
                     bool vis = stgA ? (blk_q[nq] && lg * 4 + v < a.D) : (keyA + v < lim_q[nq]);
                     x = vis ? x : -INFINITY;
@@ -149,40 +147,52 @@ __global__ __launch_bounds__(256) void attn_mfma_k(AttnArgs a)
                     bool vis = hasB && (stgB ? (blk_q[nq] && lg * 4 + v < a.D) : (keyB + v < lim_q[nq]));
                     y = vis ? y : -INFINITY;
                 }
-                sA[nq][v] = x; sB[nq][v] = y;
+                sA[v] = x; sB[v] = y;
                 mx = fmaxf(mx, fmaxf(x, y));
             }
             mx = fmaxf(mx, __shfl_xor(mx, 16));
             mx = fmaxf(mx, __shfl_xor(mx, 32));
-            m_new[nq] = fmaxf(m_run[nq], mx);
-            changed |= m_new[nq] > m_run[nq];
-        }
-        if (__any(changed)) {
-#pragma unroll
-            for (int nq = 0; nq < NQ; ++nq) {
-                float corr = m_new[nq] == -INFINITY ? 1.f : exp2f(m_run[nq] - m_new[nq]);
+            // The reference maximum only moves when it is exceeded by more than RESCALE_GAP / c (p stays below
+            // 2^RESCALE_GAP, harmless in fp32 sums and bf16 products); the accumulators are rescaled only then.
+            if (__any(mx * a.c > m_run[nq] * a.c + RESCALE_GAP || (m_run[nq] == -INFINITY && mx > -INFINITY))) {
+                const float m_new = fmaxf(m_run[nq], mx);
+                float corr = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((m_run[nq] - m_new) * a.c);
                 l_run[nq] *= corr;
 #pragma unroll
                 for (int dt = 0; dt < 8; ++dt) O[dt][nq] *= corr;
-                m_run[nq] = m_new[nq];
+                m_run[nq] = m_new;
             }
-        }
-        Op8 pop[NQ];
-#pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) {
-            float mu = m_run[nq] == -INFINITY ? 0.f : m_run[nq];
+            const float mc = m_run[nq] == -INFINITY ? 0.f : m_run[nq] * a.c;
             float p[8];
 #pragma unroll
-            for (int v = 0; v < 4; ++v) { p[v] = exp2f(sA[nq][v] - mu); p[4 + v] = exp2f(sB[nq][v] - mu); }
+            for (int v = 0; v < 4; ++v) {
+                p[v] = __builtin_amdgcn_exp2f(fmaf(sA[v], a.c, -mc));
+                p[4 + v] = __builtin_amdgcn_exp2f(fmaf(sB[v], a.c, -mc));
+            }
             l_run[nq] += (p[0] + p[1]) + (p[2] + p[3]) + (p[4] + p[5]) + (p[6] + p[7]);
-            pop[nq].w[0] = pack_bf16(p[0], p[1]); pop[nq].w[1] = pack_bf16(p[2], p[3]);
-            pop[nq].w[2] = pack_bf16(p[4], p[5]); pop[nq].w[3] = pack_bf16(p[6], p[7]);
+            Op8 pop;
+            pop.w[0] = pack_bf16(p[0], p[1]); pop.w[1] = pack_bf16(p[2], p[3]);
+            pop.w[2] = pack_bf16(p[4], p[5]); pop.w[3] = pack_bf16(p[6], p[7]);
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt)
+                O[dt][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.v[dt].v, pop.v, O[dt][nq], 0, 0, 0);
         }
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt)
-#pragma unroll
-            for (int nq = 0; nq < NQ; ++nq)
-                O[dt][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vop[dt].v, pop[nq].v, O[dt][nq], 0, 0, 0);
+    };
+    // Two register sets: while one pair is consumed the next one of this wavefront is in flight.
+    Pair t0, t1;
+    if (wave < n_pairs) load_pair(t0, wave);
+    for (int pp = wave; pp < n_pairs; pp += 8) {
+        const bool more1 = pp + 4 < n_pairs, more2 = pp + 8 < n_pairs;
+        if (more1) load_pair(t1, pp + 4);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_pair(t0, pp);
+        __builtin_amdgcn_sched_barrier(0);
+        if (more1) {
+            if (more2) load_pair(t0, pp + 8);
+            __builtin_amdgcn_sched_barrier(0);
+            compute_pair(t1, pp + 4);
+            __builtin_amdgcn_sched_barrier(0);
+        }
     }
 
     // merge the 4 wavefronts: common max per query, rescale, then a two-level sum through LDS into wavefront 0
@@ -200,7 +210,7 @@ __global__ __launch_bounds__(256) void attn_mfma_k(AttnArgs a)
     for (int nq = 0; nq < NQ; ++nq) {
         int qi = nq * 16 + ln;
         M[nq] = fmaxf(fmaxf(sm_m[0][qi], sm_m[1][qi]), fmaxf(sm_m[2][qi], sm_m[3][qi]));
-        float f = m_run[nq] == -INFINITY ? 0.f : exp2f(m_run[nq] - M[nq]);
+        float f = m_run[nq] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m_run[nq] - M[nq]) * a.c);
         if (lg == 0) sm_l[wave][qi] = l_run[nq] * f;
 #pragma unroll
         for (int dt = 0; dt < 8; ++dt) O[dt][nq] *= f;
@@ -272,7 +282,7 @@ __global__ __launch_bounds__(256) void attn_combine_k(AttnArgs a)
         f32x4 o = {0.f, 0.f, 0.f, 0.f};
         for (int c = 0; c < n_chunks; ++c) {
             float2 ml = a.part_ml[(item0 + c) * QMAX + qi];
-            float f = ml.x == -INFINITY ? 0.f : exp2f(ml.x - M);
+            float f = ml.x == -INFINITY ? 0.f : exp2f((ml.x - M) * a.c);
             L += ml.y * f;
             o += *(const f32x4 *)(a.part_o + ((item0 + c) * QMAX + qi) * HD + d4) * f;
         }

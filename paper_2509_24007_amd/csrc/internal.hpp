@@ -29,6 +29,16 @@ __host__ __device__ inline bf16_t f_to_bf16(float f)   // round to nearest even
     return (bf16_t)(c.u >> 16);
 }
 
+// two floats -> packed bf16 pair with the hardware conversion (round to nearest even)
+typedef __attribute__((ext_vector_type(2))) float sdlm_f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 sdlm_bf16x2;
+__device__ inline uint32_t pack_bf16(float lo, float hi)
+{
+    sdlm_f32x2 v = {lo, hi};
+    sdlm_bf16x2 b = __builtin_convertvector(v, sdlm_bf16x2);
+    return __builtin_bit_cast(uint32_t, b);
+}
+
 template <typename T> __device__ inline float to_f(T v);
 template <> __device__ inline float to_f<float>(float v) { return v; }
 template <> __device__ inline float to_f<bf16_t>(bf16_t v) { return bf16_to_f(v); }

@@ -211,10 +211,10 @@ __global__ __launch_bounds__(256) void gemm_mfma_k(MfmaArgs a)
                 for (int q = 0; q < 4; ++q) {
                     int n = j * 32 + q * 8 + fbase;
                     if (n >= a.N) continue;
-                    bf16_t o[4];
+                    float o[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) o[e] = f_to_bf16(silu_f(acc[0][mt][q * 4 + e]) * acc[NT - 1][mt][q * 4 + e]);
-                    *(uint2 *)(a.Yt + (size_t)r * a.n_out + n) = make_uint2(o[0] | ((uint32_t)o[1] << 16), o[2] | ((uint32_t)o[3] << 16));
+                    for (int e = 0; e < 4; ++e) o[e] = silu_f(acc[0][mt][q * 4 + e]) * acc[NT - 1][mt][q * 4 + e];
+                    *(uint2 *)(a.Yt + (size_t)r * a.n_out + n) = make_uint2(pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3]));
                 }
             }
         }
