@@ -6,17 +6,19 @@
 //   scores   S^T[key, query] = K Q^T     v_mfma_f32_16x16x32_bf16, A = one 16-key K tile, B = 16 queries
 //   output   O^T[d, query]  += V^T P^T   same instruction, A = V^T of two tiles (32 keys), B = P^T
 // The cache tiles are stored in exactly the operand order of these instructions (see internal.hpp), so a
-// wavefront loads its operands global -> registers as contiguous 1 KB / 512 B runs; nothing is staged in LDS.
+// workgroup copies a tile pair (32 keys, 16 KB) global -> LDS as one contiguous run and every wavefront reads its
+// operands from LDS with conflict-free 16-byte / 8-byte reads.  Each of the four wavefronts owns 16 of the (at
+// most 64) query vectors, so its state is small (32 accumulator registers) and four workgroups fit on a CU.
 // The mask of the method lives in registers: a pending row at position p sees cache keys [0, p]; a block row
 // sees cache keys [0, s) and the D keys of its own block (held in the sequence's staging tile).
-// The four wavefronts of a workgroup take alternate tile pairs of the chunk and merge through LDS; chunks of
-// one (group, head) are merged by a second small kernel when there is more than one.
+// Chunks of one (group, head) are merged by a second small kernel when there is more than one.
 #include "mfma.hpp"
 
 namespace sdlm {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 
 constexpr int NQ = 4;     // 16-query tiles per work item
 constexpr int QMAX = NQ * 16;
@@ -38,7 +40,7 @@ struct AttnArgs {
 
 union Op8 { bf16x8 v; uint4 u; uint2 h[2]; uint32_t w[4]; };
 
-__global__ __launch_bounds__(256) void attn_mfma_k(AttnArgs a)
+__global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
 {
     const int g = blockIdx.x, hk = blockIdx.y, chunk = blockIdx.z;
     if (g >= a.rm.counts[1]) return;
@@ -62,203 +64,141 @@ __global__ __launch_bounds__(256) void attn_mfma_k(AttnArgs a)
     const int c0 = chunk * a.chunk_pages, c1 = min(n_pages, c0 + a.chunk_pages);
     const int n_cache = c1 - c0;
     const int nv = n_cache + ((chunk == 0 && any_blk) ? 1 : 0);   // virtual tiles of this chunk; the last may be staging
+    const int n_pairs = (nv + 1) / 2;
 
-    // queries: B operands, lane (n = lane%16, group lg) holds q[32 kk + 8 lg .. +8] of query nq*16 + n
-    Op8 qop[NQ][4];
-    int lim_q[NQ], blk_q[NQ];
-#pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) {
-        int qi = nq * 16 + ln;
-        bool valid = qi < QR;
-        int rl = valid ? qi / G : 0, hg = valid ? qi % G : 0, row = row0 + rl;
-        lim_q[nq] = valid ? a.rm.lim[row] : 0;
-        blk_q[nq] = valid && a.rm.kind[row] >= 0;
-        const bf16_t *qp = a.q + ((size_t)row * a.Hq + hk * G + hg) * HD + lg * 8;
+    // This wavefront's 16 queries: B operands, lane (n = lane%16, group lg) holds q[32 kk + 8 lg .. +8] of query 16 wave + n
+    const int qi = wave * 16 + ln;
+    const bool qvalid = qi < QR;
+    const bool wave_active = wave * 16 < QR;
+    const int rl = qvalid ? qi / G : 0, hg = qvalid ? qi % G : 0, qrow = row0 + rl;
+    const int lim_q = qvalid ? a.rm.lim[qrow] : 0;
+    const bool blk_q = qvalid && a.rm.kind[qrow] >= 0;
+    Op8 qop[4];
+    {
+        const bf16_t *qp = a.q + ((size_t)qrow * a.Hq + hk * G + hg) * HD + lg * 8;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            if (valid) qop[nq][kk].u = *(const uint4 *)(qp + kk * 32);
-            else qop[nq][kk].u = make_uint4(0, 0, 0, 0);
+            qop[kk].u = make_uint4(0, 0, 0, 0);
+            if (qvalid) qop[kk].u = *(const uint4 *)(qp + kk * 32);
         }
     }
+    f32x4 O[8];
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) O[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float m_run = -INFINITY, l_run = 0.f;
 
-    f32x4 O[8][NQ];
-#pragma unroll
-    for (int dt = 0; dt < 8; ++dt)
-#pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) O[dt][nq] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_run[NQ], l_run[NQ];
-#pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) { m_run[nq] = -INFINITY; l_run[nq] = 0.f; }
-
+    // K/V of one tile pair (32 keys, 16 KB) is fetched by the whole workgroup, 64 bytes per thread, and shared
+    // through LDS in the cache's own operand order; two LDS buffers, the next pair rides in registers meanwhile.
+    __shared__ __attribute__((aligned(16))) bf16_t kv[2][2][2 * PAGE * HD];   // [buffer][tile A/B][K block | V block]
     const int32_t *ptab = a.st.page_table + (size_t)b * a.kg.pages_per_seq;
     const size_t tile_elems = 2 * PAGE * HD;
-    const int n_pairs = (nv + 1) / 2;
     const int stg_page = a.kg.staging_base + b;
-
-    // One pair of tiles (32 keys): K operands of both tiles, V^T operands with the two tiles side by side.
-    struct Pair { Op8 kA[4], kB[4], v[8]; };
-    // Request pair pp: 16 KB per wavefront, global -> registers.  An absent second tile aliases the first.
-    auto load_pair = [&](Pair &t, int pp) {
+    u32x4 r[4];
+    auto fetch = [&](int pp) {
         const int uA = 2 * pp, uB = 2 * pp + 1;
-        const bool hasB = uB < nv;
         const int pgA = uA >= n_cache ? stg_page : ptab[c0 + uA];
-        const int pgB = !hasB ? pgA : (uB >= n_cache ? stg_page : ptab[c0 + uB]);
+        const int pgB = uB >= nv ? pgA : (uB >= n_cache ? stg_page : ptab[c0 + uB]);
         const bf16_t *tA = a.pool + ((size_t)pgA * a.kg.n_kv_heads + hk) * tile_elems;
         const bf16_t *tB = a.pool + ((size_t)pgB * a.kg.n_kv_heads + hk) * tile_elems;
-#pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            t.kA[kk].u = *(const uint4 *)(tA + (kk * 64 + lane) * 8);
-            t.kB[kk].u = *(const uint4 *)(tB + (kk * 64 + lane) * 8);
-        }
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt) {
-            t.v[dt].h[0] = *(const uint2 *)(tA + PAGE * HD + (dt * 64 + lane) * 4);
-            t.v[dt].h[1] = *(const uint2 *)(tB + PAGE * HD + (dt * 64 + lane) * 4);
-        }
+        r[0] = *(const u32x4 *)(tA + tid * 8);
+        r[1] = *(const u32x4 *)(tA + (256 + tid) * 8);
+        r[2] = *(const u32x4 *)(tB + tid * 8);
+        r[3] = *(const u32x4 *)(tB + (256 + tid) * 8);
     };
-    // Scores, mask, online softmax and P V for one pair, one 16-query tile at a time.
-    auto compute_pair = [&](Pair &t, int pp) {
-        const int uA = 2 * pp, uB = 2 * pp + 1;
-        const bool hasB = uB < nv;
-        const bool stgA = uA >= n_cache, stgB = hasB && uB >= n_cache;
-        const int keyA = (c0 + uA) * PAGE + lg * 4, keyB = (c0 + uB) * PAGE + lg * 4;
-        const bool fullA = !stgA && (c0 + uA + 1) * PAGE <= min_lim;
-        const bool fullB = hasB && !stgB && (c0 + uB + 1) * PAGE <= min_lim;
-#pragma unroll
-        for (int nq = 0; nq < NQ; ++nq) {
-            if (nq * 16 >= QR) continue;
-            // lane (query n, group lg) gets keys 4 lg .. 4 lg + 3 of each tile
+    auto stash = [&](int buf) {
+        *(u32x4 *)(&kv[buf][0][0] + tid * 8) = r[0];
+        *(u32x4 *)(&kv[buf][0][0] + (256 + tid) * 8) = r[1];
+        *(u32x4 *)(&kv[buf][1][0] + tid * 8) = r[2];
+        *(u32x4 *)(&kv[buf][1][0] + (256 + tid) * 8) = r[3];
+    };
+    fetch(0);
+    stash(0);
+    __syncthreads();
+    for (int pp = 0; pp < n_pairs; ++pp) {
+        const int buf = pp & 1;
+        if (pp + 1 < n_pairs) fetch(pp + 1);
+        if (wave_active) {
+            const int uA = 2 * pp, uB = 2 * pp + 1;
+            const bool hasB = uB < nv;
+            const bool stgA = uA >= n_cache, stgB = hasB && uB >= n_cache;
+            const bf16_t *KA = &kv[buf][0][0], *KB = &kv[buf][1][0];
+            // scores: lane (query n, group lg) gets keys 4 lg .. 4 lg + 3 of each tile
             f32x4 sA = {0.f, 0.f, 0.f, 0.f}, sB = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) {
-                sA = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.kA[kk].v, qop[nq][kk].v, sA, 0, 0, 0);
-                sB = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.kB[kk].v, qop[nq][kk].v, sB, 0, 0, 0);
+                Op8 ka, kb;
+                ka.u = *(const uint4 *)(KA + (kk * 64 + lane) * 8);
+                kb.u = *(const uint4 *)(KB + (kk * 64 + lane) * 8);
+                sA = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ka.v, qop[kk].v, sA, 0, 0, 0);
+                sB = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kb.v, qop[kk].v, sB, 0, 0, 0);
+            }
+            const bool fullA = !stgA && (c0 + uA + 1) * PAGE <= min_lim;
+            const bool fullB = hasB && !stgB && (c0 + uB + 1) * PAGE <= min_lim;
+            if (!(fullA && fullB)) {
+                const int keyA = (c0 + uA) * PAGE + lg * 4, keyB = (c0 + uB) * PAGE + lg * 4;
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    bool visA = stgA ? (blk_q && lg * 4 + v < a.D) : (keyA + v < lim_q);
+                    bool visB = hasB && (stgB ? (blk_q && lg * 4 + v < a.D) : (keyB + v < lim_q));
+                    sA[v] = visA ? sA[v] : -INFINITY;
+                    sB[v] = visB ? sB[v] : -INFINITY;
+                }
             }
             // raw scores; the softmax scale is folded into the exponent: p = 2^(c s - c m)
-            float mx = -INFINITY;
-#pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                float x = sA[v], y = sB[v];
-                if (!fullA) {
-                    bool vis = stgA ? (blk_q[nq] && lg * 4 + v < a.D) : (keyA + v < lim_q[nq]);
-                    x = vis ? x : -INFINITY;
-                }
-                if (!fullB) {
-                    bool vis = hasB && (stgB ? (blk_q[nq] && lg * 4 + v < a.D) : (keyB + v < lim_q[nq]));
-                    y = vis ? y : -INFINITY;
-                }
-                sA[v] = x; sB[v] = y;
-                mx = fmaxf(mx, fmaxf(x, y));
-            }
+            float mx = fmaxf(fmaxf(fmaxf(sA[0], sA[1]), fmaxf(sA[2], sA[3])), fmaxf(fmaxf(sB[0], sB[1]), fmaxf(sB[2], sB[3])));
             mx = fmaxf(mx, __shfl_xor(mx, 16));
             mx = fmaxf(mx, __shfl_xor(mx, 32));
             // The reference maximum only moves when it is exceeded by more than RESCALE_GAP / c (p stays below
             // 2^RESCALE_GAP, harmless in fp32 sums and bf16 products); the accumulators are rescaled only then.
-            if (__any(mx * a.c > m_run[nq] * a.c + RESCALE_GAP || (m_run[nq] == -INFINITY && mx > -INFINITY))) {
-                const float m_new = fmaxf(m_run[nq], mx);
-                float corr = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((m_run[nq] - m_new) * a.c);
-                l_run[nq] *= corr;
+            if (__any((mx - m_run) * a.c > RESCALE_GAP || (m_run == -INFINITY && mx > -INFINITY))) {
+                const float m_new = fmaxf(m_run, mx);
+                const float corr = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f((m_run - m_new) * a.c);
+                l_run *= corr;
 #pragma unroll
-                for (int dt = 0; dt < 8; ++dt) O[dt][nq] *= corr;
-                m_run[nq] = m_new;
+                for (int dt = 0; dt < 8; ++dt) O[dt] *= corr;
+                m_run = m_new;
             }
-            const float mc = m_run[nq] == -INFINITY ? 0.f : m_run[nq] * a.c;
+            const float mc = m_run == -INFINITY ? 0.f : m_run * a.c;
             float p[8];
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 p[v] = __builtin_amdgcn_exp2f(fmaf(sA[v], a.c, -mc));
                 p[4 + v] = __builtin_amdgcn_exp2f(fmaf(sB[v], a.c, -mc));
             }
-            l_run[nq] += (p[0] + p[1]) + (p[2] + p[3]) + (p[4] + p[5]) + (p[6] + p[7]);
+            l_run += (p[0] + p[1]) + (p[2] + p[3]) + (p[4] + p[5]) + (p[6] + p[7]);
             Op8 pop;
             pop.w[0] = pack_bf16(p[0], p[1]); pop.w[1] = pack_bf16(p[2], p[3]);
             pop.w[2] = pack_bf16(p[4], p[5]); pop.w[3] = pack_bf16(p[6], p[7]);
+            const bf16_t *VA = KA + PAGE * HD, *VB = KB + PAGE * HD;
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt)
-                O[dt][nq] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.v[dt].v, pop.v, O[dt][nq], 0, 0, 0);
-        }
-    };
-    // Two register sets: while one pair is consumed the next one of this wavefront is in flight.
-    Pair t0, t1;
-    if (wave < n_pairs) load_pair(t0, wave);
-    for (int pp = wave; pp < n_pairs; pp += 8) {
-        const bool more1 = pp + 4 < n_pairs, more2 = pp + 8 < n_pairs;
-        if (more1) load_pair(t1, pp + 4);
-        __builtin_amdgcn_sched_barrier(0);
-        compute_pair(t0, pp);
-        __builtin_amdgcn_sched_barrier(0);
-        if (more1) {
-            if (more2) load_pair(t0, pp + 8);
-            __builtin_amdgcn_sched_barrier(0);
-            compute_pair(t1, pp + 4);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-    }
-
-    // merge the 4 wavefronts: common max per query, rescale, then a two-level sum through LDS into wavefront 0
-    __shared__ float sm_m[4][QMAX], sm_l[4][QMAX];
-    __shared__ __attribute__((aligned(16))) float sm_o[2][QMAX][HD + 4];
-#pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) {
-        l_run[nq] += __shfl_xor(l_run[nq], 16);
-        l_run[nq] += __shfl_xor(l_run[nq], 32);
-        if (lg == 0) sm_m[wave][nq * 16 + ln] = m_run[nq];
-    }
-    __syncthreads();
-    float M[NQ];
-#pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) {
-        int qi = nq * 16 + ln;
-        M[nq] = fmaxf(fmaxf(sm_m[0][qi], sm_m[1][qi]), fmaxf(sm_m[2][qi], sm_m[3][qi]));
-        float f = m_run[nq] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f((m_run[nq] - M[nq]) * a.c);
-        if (lg == 0) sm_l[wave][qi] = l_run[nq] * f;
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt) O[dt][nq] *= f;
-    }
-    if (wave >= 2) {
-#pragma unroll
-        for (int nq = 0; nq < NQ; ++nq)
-#pragma unroll
-            for (int dt = 0; dt < 8; ++dt) *(f32x4 *)&sm_o[wave - 2][nq * 16 + ln][dt * 16 + lg * 4] = O[dt][nq];
-    }
-    __syncthreads();
-    if (wave < 2) {
-#pragma unroll
-        for (int nq = 0; nq < NQ; ++nq)
-#pragma unroll
-            for (int dt = 0; dt < 8; ++dt) O[dt][nq] += *(f32x4 *)&sm_o[wave][nq * 16 + ln][dt * 16 + lg * 4];
-    }
-    __syncthreads();
-    if (wave == 1) {
-#pragma unroll
-        for (int nq = 0; nq < NQ; ++nq)
-#pragma unroll
-            for (int dt = 0; dt < 8; ++dt) *(f32x4 *)&sm_o[0][nq * 16 + ln][dt * 16 + lg * 4] = O[dt][nq];
-    }
-    __syncthreads();
-    if (wave != 0) return;
-    const bool single = n_chunks == 1;
-    const size_t item = ((size_t)g * a.kg.n_kv_heads + hk) * a.max_chunks + chunk;
-#pragma unroll
-    for (int nq = 0; nq < NQ; ++nq) {
-        int qi = nq * 16 + ln;
-        if (qi >= QR) continue;
-        float L = sm_l[0][qi] + sm_l[1][qi] + sm_l[2][qi] + sm_l[3][qi];
-        float inv = single ? 1.0f / L : 1.0f;
-        int rl = qi / G, hg = qi % G;
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt) {
-            f32x4 o = (O[dt][nq] + *(f32x4 *)&sm_o[0][qi][dt * 16 + lg * 4]) * inv;
-            int d4 = dt * 16 + lg * 4;
-            if (single) {
-                bf16_t *op = a.out + ((size_t)(row0 + rl) * a.Hq + hk * G + hg) * HD + d4;
-                *(uint2 *)op = make_uint2(pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3]));
-            } else {
-                *(f32x4 *)(a.part_o + (item * QMAX + qi) * HD + d4) = o;
+            for (int dt = 0; dt < 8; ++dt) {
+                Op8 vo;
+                vo.h[0] = *(const uint2 *)(VA + (dt * 64 + lane) * 4);
+                vo.h[1] = *(const uint2 *)(VB + (dt * 64 + lane) * 4);
+                O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vo.v, pop.v, O[dt], 0, 0, 0);
             }
         }
-        if (!single && lg == 0) a.part_ml[item * QMAX + qi] = make_float2(M[nq], L);
+        if (pp + 1 < n_pairs) stash(buf ^ 1);
+        __syncthreads();
     }
+    if (!qvalid) return;
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+    const bool single = n_chunks == 1;
+    const size_t item = ((size_t)g * a.kg.n_kv_heads + hk) * a.max_chunks + chunk;
+    const float inv = single ? 1.0f / l_run : 1.0f;
+#pragma unroll
+    for (int dt = 0; dt < 8; ++dt) {
+        f32x4 o = O[dt] * inv;
+        const int d4 = dt * 16 + lg * 4;
+        if (single) {
+            bf16_t *op = a.out + ((size_t)qrow * a.Hq + hk * G + hg) * HD + d4;
+            *(uint2 *)op = make_uint2(pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3]));
+        } else {
+            *(f32x4 *)(a.part_o + (item * QMAX + qi) * HD + d4) = o;
+        }
+    }
+    if (!single && lg == 0) a.part_ml[item * QMAX + qi] = make_float2(m_run, l_run);
 }
 
 // Merge the chunks of one (group, kv head): out = sum_c 2^{m_c - M} o_c / sum_c 2^{m_c - M} l_c.
