@@ -141,7 +141,7 @@ int sdlm_decode_step(sdlm_ctx *ctx, int32_t *ids, int32_t *count, float *conf, f
  * become the next step's pending tokens (n_b += count_b); in the paged layout the page table grows to back
  * every position < n_b.  With both arguments NULL the step's own result is committed.  With ids_override
  * [dev, batch x D] and count_override [dev, batch] (1 <= count <= D; out-of-range counts are clamped and
- * reported through sdlm_get_lengths' return code) the caller's tokens are committed instead: this is how a
+ * reported through sdlm_get_lengths' return code, as are override ids outside the vocabulary, which are replaced by 0) the caller's tokens are committed instead: this is how a
  * verifier or a teacher-forced test drives the cache.  Errors: SDLM_ESTATE without a preceding step.
  */
 int sdlm_kv_commit(sdlm_ctx *ctx, const int32_t *ids_override, const int32_t *count_override);

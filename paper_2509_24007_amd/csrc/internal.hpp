@@ -71,7 +71,7 @@ struct SeqState {
     int32_t *pend_tok;              // [B][D]: tokens at positions c..n-1
     int32_t *page_table;            // [B][pages_per_seq]
     int32_t *pages_backed;          // [B]
-    int32_t *alloc;                 // [0] next free page, [1] error bits (1: pool exhausted, 2: count clamped)
+    int32_t *alloc;                 // [0] next free page, [1] error bits (1: pool exhausted, 2: count clamped, 4: bad override id)
     int32_t *last_ids, *last_count; // [B][D], [B]: the last step's result
 };
 
@@ -97,7 +97,7 @@ struct GemmArgs {
 };
 
 void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows);
-void launch_embed(hipStream_t s, int dtype, float *x, const void *E, const RowMeta &rm, int max_rows, int h);
+void launch_embed(hipStream_t s, int dtype, float *x, const void *E, const RowMeta &rm, int max_rows, int h, int V);
 void launch_rmsnorm(hipStream_t s, int dtype, void *out, const float *x, const void *g, int h, float eps,
                     const int32_t *row_index, const int32_t *p_count, int max_rows);
 void launch_gemm_generic(hipStream_t s, int dtype, int epi, const GemmArgs &a);
@@ -110,7 +110,7 @@ void launch_lm_reduce(hipStream_t s, const float *logits, int V, int32_t *ids, f
 void launch_accept(hipStream_t s, const SeqState &st, const int32_t *ids_rows, const float *conf_rows, int B, int D,
                    float tau, int rule, int32_t *ids_out, int32_t *count_out, float *conf_out);
 void launch_commit(hipStream_t s, const SeqState &st, int B, int D, const int32_t *ids_ovr, const int32_t *cnt_ovr,
-                   int paged, int n_pages, int pages_per_seq);
+                   int paged, int n_pages, int pages_per_seq, int V);
 void launch_read_kv(hipStream_t s, int dtype, const void *pool_layer, const KvGeom &kg, const SeqState &st, int seq,
                     int kvh, int pos0, int count, float *k_out, float *v_out);
 

@@ -52,18 +52,18 @@ void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm
 
 // ------------------------------------------------------------------------------------------------ embedding
 template <typename T>
-__global__ void embed_k(float *x, const T *E, const int32_t *tok, const int32_t *pR, int h)
+__global__ void embed_k(float *x, const T *E, const int32_t *tok, const int32_t *pR, int h, int V)
 {
     int r = blockIdx.x;
     if (r >= *pR) return;
-    const T *e = E + (size_t)tok[r] * h;
+    const T *e = E + (size_t)min(max(tok[r], 0), V - 1) * h;
     for (int k = threadIdx.x; k < h; k += blockDim.x) x[(size_t)r * h + k] = to_f<T>(e[k]);
 }
 
-void launch_embed(hipStream_t s, int dtype, float *x, const void *E, const RowMeta &rm, int max_rows, int h)
+void launch_embed(hipStream_t s, int dtype, float *x, const void *E, const RowMeta &rm, int max_rows, int h, int V)
 {
-    if (dtype == 0) hipLaunchKernelGGL(embed_k<float>, dim3(max_rows), dim3(256), 0, s, x, (const float *)E, rm.tok, rm.counts, h);
-    else hipLaunchKernelGGL(embed_k<bf16_t>, dim3(max_rows), dim3(256), 0, s, x, (const bf16_t *)E, rm.tok, rm.counts, h);
+    if (dtype == 0) hipLaunchKernelGGL(embed_k<float>, dim3(max_rows), dim3(256), 0, s, x, (const float *)E, rm.tok, rm.counts, h, V);
+    else hipLaunchKernelGGL(embed_k<bf16_t>, dim3(max_rows), dim3(256), 0, s, x, (const bf16_t *)E, rm.tok, rm.counts, h, V);
 }
 
 // ------------------------------------------------------------------------------------------------ RMSNorm
@@ -311,7 +311,7 @@ __global__ __launch_bounds__(256) void lm_reduce_k(const float *logits, int V, i
     __shared__ int si[4];
     __shared__ float red[4];
     float m = -INFINITY;
-    int arg = 0x7fffffff;
+    int arg = 0;   // stays a valid id even if every logit is NaN
     for (int v = threadIdx.x; v < V; v += 256) {
         float t = z[v];
         if (t > m) { m = t; arg = v; }
@@ -386,7 +386,7 @@ void launch_accept(hipStream_t s, const SeqState &st, const int32_t *ids_rows, c
 // c <- n (the pending K/V, already in place, become cache); the accepted tokens become the pending tokens;
 // n <- n + count; the page table grows so that every position < n is backed.
 __global__ void commit_k(SeqState st, int B, int D, const int32_t *ids_ovr, const int32_t *cnt_ovr, int paged, int n_pages,
-                         int pages_per_seq)
+                         int pages_per_seq, int V)
 {
     int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
@@ -402,16 +402,20 @@ __global__ void commit_k(SeqState st, int B, int D, const int32_t *ids_ovr, cons
         for (int i = 0; i < need; ++i) st.page_table[(size_t)b * pages_per_seq + st.pages_backed[b] + i] = first + i;
         st.pages_backed[b] += need;
     }
-    for (int i = 0; i < cnt; ++i) st.pend_tok[b * D + i] = ids[i];
-    st.last_tok[b] = ids[cnt - 1];
+    for (int i = 0; i < cnt; ++i) {
+        int id = ids[i];
+        if (id < 0 || id >= V) { atomicOr(&st.alloc[1], 4); id = 0; }   // an override token outside the vocabulary
+        st.pend_tok[b * D + i] = id;
+    }
+    st.last_tok[b] = st.pend_tok[b * D + cnt - 1];
     st.c[b] = n;
     st.n[b] = n_new;
 }
 
 void launch_commit(hipStream_t s, const SeqState &st, int B, int D, const int32_t *ids_ovr, const int32_t *cnt_ovr,
-                   int paged, int n_pages, int pages_per_seq)
+                   int paged, int n_pages, int pages_per_seq, int V)
 {
-    hipLaunchKernelGGL(commit_k, dim3((B + 63) / 64), dim3(64), 0, s, st, B, D, ids_ovr, cnt_ovr, paged, n_pages, pages_per_seq);
+    hipLaunchKernelGGL(commit_k, dim3((B + 63) / 64), dim3(64), 0, s, st, B, D, ids_ovr, cnt_ovr, paged, n_pages, pages_per_seq, V);
 }
 
 // ------------------------------------------------------------------------------------------------ debug read-back

@@ -140,17 +140,29 @@ __global__ __launch_bounds__(256) void gemm_mfma_k(MfmaArgs a)
 
     const int brow = lane & 31, bk = (lane >> 5) * 8;
     int buf = 0;
+/* one k-step: request the LDS operands of the next k-step, run this k-step's MFMAs, and pin that order */
+#define SDLM_KSTEP(WC, ks, has_next)                                                                              \
+    {                                                                                                             \
+        if (has_next) {                                                                                           \
+            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                                    \
+                bn_[mt] = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][((ks) + 1) * 16 + bk];                        \
+        }                                                                                                         \
+        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                                        \
+            _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                    \
+                acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WC[nt][ks], bc_[mt], acc[nt][mt], 0, 0, 0); \
+        __builtin_amdgcn_sched_group_barrier(0x100, (has_next) ? MT : 0, 0);                                      \
+        __builtin_amdgcn_sched_group_barrier(0x008, MT * NT, 0);                                                  \
+        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) bc_[mt] = bn_[mt];                                     \
+    }
 #define SDLM_STAGE(WC, WN, stage)                                                                                 \
     if ((stage) < s_end) {                                                                                        \
         SDLM_LOAD_X((stage) + 1);                                                                                 \
         SDLM_LOAD_W(WN, (stage) + 2);                                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                                        \
-        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                                         \
-            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                                  \
-                bf16x8 b_ = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][ks * 16 + bk];                              \
-                _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                \
-                    acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WC[nt][ks], b_, acc[nt][mt], 0, 0, 0);  \
-            }                                                                                                     \
+        bf16x8 bc_[MT], bn_[MT];                                                                                  \
+        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) bc_[mt] = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][bk]; \
+        __builtin_amdgcn_sched_group_barrier(0x100, MT, 0);                                                       \
+        SDLM_KSTEP(WC, 0, 1) SDLM_KSTEP(WC, 1, 1) SDLM_KSTEP(WC, 2, 1) SDLM_KSTEP(WC, 3, 0)                       \
         __builtin_amdgcn_sched_barrier(0);                                                                        \
         _Pragma("unroll") for (int i = 0; i < MT; ++i) *(u32x4 *)&Xs[buf ^ 1][i * 32 + xrow][xchunk * 8] = xr[i]; \
         buf ^= 1;                                                                                                 \
@@ -162,6 +174,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_k(MfmaArgs a)
         SDLM_STAGE(w2, w1, s + 2)
     }
 #undef SDLM_STAGE
+#undef SDLM_KSTEP
 #undef SDLM_LOAD_W
 #undef SDLM_LOAD_X
 
@@ -227,7 +240,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_k(MfmaArgs a)
         for (int mt = 0; mt < MT; ++mt) {
             const int r = m0 + mt * 32 + brow;
             float m = -INFINITY;
-            int arg = 0x7fffffff;
+            int arg = 0;   // stays a valid id even if every logit is NaN
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -312,7 +325,7 @@ __global__ __launch_bounds__(256) void lm_combine_k(const float4 *part, int n_bl
     __shared__ int sa[4];
     __shared__ float red[4];
     float m = -INFINITY;
-    int arg = 0x7fffffff;
+    int arg = 0;
     for (int i = threadIdx.x; i < n_blocks; i += 256) {
         float4 p = part[(size_t)i * max_rows + r];
         int a = __float_as_int(p.w);

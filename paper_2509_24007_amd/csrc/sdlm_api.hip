@@ -215,7 +215,7 @@ void run_layers(sdlm_ctx *c, int rows, int groups)
     const int nq = m.n_q_heads * d, nk = m.n_kv_heads * d, nqkv = nq + 2 * nk;
     const size_t e = c->L.esz;
     hipStream_t s = c->stream;
-    { Phase p(c, SDLM_PH_ROWS); launch_embed(s, dt, c->x, c->embed, c->rm, rows, h); }
+    { Phase p(c, SDLM_PH_ROWS); launch_embed(s, dt, c->x, c->embed, c->rm, rows, h, m.vocab); }
     for (int l = 0; l < m.n_layers; ++l) {
         const LayerW &w = c->lw[l];
         char *pool_l = c->pool + (size_t)l * c->kg.layer_stride * e;
@@ -547,7 +547,7 @@ int sdlm_kv_commit(sdlm_ctx *c, const int32_t *ids_override, const int32_t *coun
             if (pages() > c->L.n_pages) return fail(c, SDLM_ECAPACITY, "page pool (%d pages) would be exhausted", c->L.n_pages);
         }
     }
-    launch_commit(c->stream, c->st, B, D, ids_override, count_override, c->r.kv_layout, c->L.n_pages, c->L.pages_per_seq);
+    launch_commit(c->stream, c->st, B, D, ids_override, count_override, c->r.kv_layout, c->L.n_pages, c->L.pages_per_seq, c->m.vocab);
     HIPCHK(c, hipGetLastError());
     for (int b = 0; b < B; ++b) c->n_ub[b] += D;
     c->stepped = false;
@@ -568,6 +568,7 @@ int sdlm_get_lengths(sdlm_ctx *c, int32_t *n, int32_t *cc)
         HIPCHK(c, hipMemcpyAsync(c->st.alloc + 1, &zero, 4, hipMemcpyHostToDevice, c->stream));
         HIPCHK(c, hipStreamSynchronize(c->stream));
         if (flags & 1) return fail(c, SDLM_ECAPACITY, "a sequence could not grow: page pool or max_seq_len exhausted");
+        if (flags & 4) return fail(c, SDLM_EINVAL, "an override token id outside the vocabulary was replaced by 0");
         return fail(c, SDLM_EINVAL, "an override count outside 1..D was clamped");
     }
     return SDLM_OK;

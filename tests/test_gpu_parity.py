@@ -171,6 +171,16 @@ def test_error_paths():
     with pytest.raises(sdlm.SdlmError) as e:
         ctx.get_lengths()
     assert e.value.code == sdlm.EINVAL
+    # an override token outside the vocabulary is replaced and reported
+    ctx.prefill([[1, 2, 3]])
+    ctx.decode_step(ids, cnt)
+    bad = torch.full((2, 4), m.vocab + 5, dtype=torch.int32, device="cuda")
+    ctx.kv_commit(bad, torch.ones(2, dtype=torch.int32, device="cuda"))
+    with pytest.raises(sdlm.SdlmError) as e:
+        ctx.get_lengths()
+    assert e.value.code == sdlm.EINVAL
+    ctx.decode_step(ids, cnt)                               # and the next step still runs on valid rows
+    torch.cuda.synchronize()
     ctx.close()
     # paged pool too small for the prompts
     ctx = gpu_context(m, g_dev, layers_dev, max_batch=2, max_seq_len=64, D=4, tau=0.5, paged=True, n_pages=2)
@@ -183,6 +193,26 @@ def test_error_paths():
             ctx.decode_step(ids, cnt)
             ctx.kv_commit(toks, four)
     assert e.value.code == sdlm.ECAPACITY
+    ctx.close()
+
+
+@pytest.mark.parametrize("dtype,hd", [("fp32", 32), ("bf16", 128)])
+def test_nan_logits_still_give_valid_ids(dtype, hd):
+    """Non-finite weights must not turn into out-of-range token ids (they would index the embedding table)."""
+    m = gpu_cfg(dtype=dtype, head_dim=hd, hidden=128, ffn=128, n_q_heads=2, n_kv_heads=1) if dtype == "fp32" else mfma_cfg()
+    om, g_dev, layers_dev = both_models(m, seed=12, std=0.05)
+    g_dev = dict(g_dev)
+    g_dev["lm_head"] = torch.full_like(g_dev["lm_head"], float("nan"))
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=2, max_seq_len=64, D=4, tau=0.5)
+    ctx.prefill([[1, 2, 3], [4]])
+    ids = torch.empty(2, 4, dtype=torch.int32, device="cuda")
+    cnt = torch.empty(2, dtype=torch.int32, device="cuda")
+    for _ in range(3):
+        ctx.decode_step(ids, cnt)
+        ctx.kv_commit()
+    torch.cuda.synchronize()
+    assert int(ids.min()) >= 0 and int(ids.max()) < m.vocab
+    assert int(cnt.min()) >= 1 and int(cnt.max()) <= 4
     ctx.close()
 
 
@@ -207,6 +237,7 @@ def mfma_cfg(**kw):
     ("g7-ragged-vocab", dict(n_q_heads=14, n_kv_heads=2, vocab=1000, ffn=320), [3, 17, 33, 64, 70], 4, 0.6, True),
     ("g8-D8-two-groups", dict(n_q_heads=16, n_kv_heads=2, hidden=512), [5, 130, 300], 8, 0.5, False),
     ("g6-D4-batch1-long", dict(n_q_heads=12, n_kv_heads=2, hidden=384, ffn=1024), [700], 4, 0.6, False),
+    ("g4-batch20-128-row-tiles", dict(n_q_heads=8, n_kv_heads=2, vocab=4096 + 160), [3 + 7 * i for i in range(20)], 4, 0.6, True),
     ("g5-D16", dict(n_q_heads=10, n_kv_heads=2, hidden=320, ffn=640, has_qkv_bias=False), [2, 50], 16, 0.3, True),
 ])
 def test_bf16_mfma_path(name, kw, lens, D, tau, paged):
