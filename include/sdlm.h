@@ -161,6 +161,7 @@ int sdlm_get_lengths(sdlm_ctx *ctx, int32_t *n, int32_t *c);
  *   3: residual stream leaving the layer             float [R, hidden]
  *   4: normalised block rows entering the LM head    elem  [batch*D, hidden]   (layer ignored)
  *   5: rotated queries                               elem  [R, Hq*d]
+ *   6: residual stream after the O projection        float [R, hidden]
  * "elem" is float in fp32 mode and bf16 in bf16 mode.  R is the step's packed row count: per sequence its
  * pending rows then its D block rows.  `which` < 0 clears all taps.  dst must hold max_rows rows.
  */
@@ -174,7 +175,8 @@ int sdlm_debug_rows(sdlm_ctx *ctx, int32_t *tok, int32_t *pos, int32_t *seq, int
 
 /*
  * Read cached K and V vectors of one (layer, sequence, kv head) for positions [pos0, pos0+count) into
- * k_out, v_out [dev, count x head_dim] as float.  Positions must be < n_b.
+ * k_out, v_out [dev, count x head_dim] as float.  Positions must be < n_b.  pos0 = -1 reads instead the first
+ * `count` (<= D) entries of the sequence's staging tile: the K/V of the last step's block rows at that layer.
  */
 int sdlm_debug_read_kv(sdlm_ctx *ctx, int32_t layer, int32_t seq, int32_t kv_head, int32_t pos0, int32_t count,
                        float *k_out, float *v_out);

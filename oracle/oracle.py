@@ -29,7 +29,7 @@ def build(force: bool = False) -> str:
 class _Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn",
                                          "vocab", "mask_token_id", "has_qkv_bias", "wdtype")] + \
-               [(n, C.c_double) for n in ("rope_theta", "rms_eps", "logit_scale")]
+               [(n, C.c_double) for n in ("rope_theta", "rms_eps", "logit_scale")] + [("bf16_points", C.c_int32)]
 
 
 _PP = C.POINTER(C.c_void_p)
@@ -88,6 +88,8 @@ def lib():
         L.orc_seq_read_kv.argtypes = [vp, i32, i32, i32, vp, vp]
         L.orc_probe_logit.restype = f64
         L.orc_probe_logit.argtypes = [vp, vp, vp, i32]
+        L.orc_probe_logits_row.restype = None
+        L.orc_probe_logits_row.argtypes = [vp, vp, vp, vp]
         L.orc_probe_linear.restype = f64
         L.orc_probe_linear.argtypes = [vp, vp, i32, vp, i32, i32]
         L.orc_probe_attend.restype = None
@@ -96,6 +98,8 @@ def lib():
         L.orc_probe_rmsnorm.argtypes = [vp, vp, i32, i32, f64, vp]
         L.orc_probe_rope.restype = None
         L.orc_probe_rope.argtypes = [vp, i32, i32, f64]
+        L.orc_probe_round_bf16.restype = f64
+        L.orc_probe_round_bf16.argtypes = [f64]
         L.orc_probe_silu.restype = f64
         L.orc_probe_silu.argtypes = [f64]
         _lib = L
@@ -124,7 +128,7 @@ class Model:
 
     def __init__(self, *, n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab,
                  rope_theta, rms_eps, logit_scale, mask_token_id, has_qkv_bias,
-                 globals_: Dict[str, object], layers: Sequence[Dict[str, object]]):
+                 globals_: Dict[str, object], layers: Sequence[Dict[str, object]], bf16_points: bool = False):
         self.vocab, self.hidden, self.n_layers = vocab, hidden, n_layers
         self.head_dim, self.n_kv_heads, self.n_q_heads = head_dim, n_kv_heads, n_q_heads
         self._keep: List[np.ndarray] = []
@@ -132,7 +136,7 @@ class Model:
         wdtype = 0 if emb.dtype == np.float32 else 1
         self.wdtype = wdtype
         self.cfg = _Cfg(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, mask_token_id,
-                        int(bool(has_qkv_bias)), wdtype, rope_theta, rms_eps, logit_scale)
+                        int(bool(has_qkv_bias)), wdtype, rope_theta, rms_eps, logit_scale, int(bool(bf16_points)))
         self.w = _Weights()
         self.arrays: Dict[str, object] = {}
         for name in ("embed", "lm_head", "final_norm"):
@@ -158,6 +162,9 @@ class Model:
             self._tables.append(tab)
             setattr(self.w, name, C.cast(tab, _PP))
 
+    def set_bf16_points(self, on: bool) -> None:
+        self.cfg.bf16_points = int(bool(on))
+
     @property
     def cfg_p(self):
         return C.addressof(self.cfg)
@@ -167,12 +174,15 @@ class Model:
         return C.addressof(self.w)
 
 
-def model_from_inputs(mcfg, globals_, layers) -> Model:
-    """Build an oracle Model from the synthetic-input module's ModelCfg and tensors."""
+def model_from_inputs(mcfg, globals_, layers, bf16_points: bool = False) -> Model:
+    """Build an oracle Model from the synthetic-input module's ModelCfg and tensors.
+
+    bf16_points=True makes the oracle round activations to bf16 at the points where a bf16 pipeline must
+    (see round_rows in the C file); the default keeps every intermediate in double."""
     return Model(n_layers=mcfg.n_layers, hidden=mcfg.hidden, n_q_heads=mcfg.n_q_heads, n_kv_heads=mcfg.n_kv_heads,
                  head_dim=mcfg.head_dim, ffn=mcfg.ffn, vocab=mcfg.vocab, rope_theta=mcfg.rope_theta,
                  rms_eps=mcfg.rms_eps, logit_scale=mcfg.logit_scale, mask_token_id=mcfg.mask_token_id,
-                 has_qkv_bias=mcfg.has_qkv_bias, globals_=globals_, layers=layers)
+                 has_qkv_bias=mcfg.has_qkv_bias, globals_=globals_, layers=layers, bf16_points=bf16_points)
 
 
 def _i32(a) -> np.ndarray:
@@ -308,6 +318,13 @@ def probe_logit(model: Model, xhat, v: int) -> float:
     return float(lib().orc_probe_logit(model.cfg_p, model.w_p, _ptr(x), int(v)))
 
 
+def probe_logits_row(model: Model, xhat) -> np.ndarray:
+    x = np.ascontiguousarray(xhat, dtype=np.float64)
+    out = np.empty(model.vocab, dtype=np.float64)
+    lib().orc_probe_logits_row(model.cfg_p, model.w_p, _ptr(x), _ptr(out))
+    return out
+
+
 def probe_linear(W: np.ndarray, b: Optional[np.ndarray], x, o: int) -> float:
     x = np.ascontiguousarray(x, dtype=np.float64)
     wdtype = 0 if W.dtype == np.float32 else 1
@@ -335,6 +352,10 @@ def probe_rope(v, pos: int, theta: float) -> np.ndarray:
     v = np.array(v, dtype=np.float64)
     lib().orc_probe_rope(_ptr(v), v.size, int(pos), float(theta))
     return v
+
+
+def probe_round_bf16(x: float) -> float:
+    return float(lib().orc_probe_round_bf16(float(x)))
 
 
 def probe_silu(x: float) -> float:

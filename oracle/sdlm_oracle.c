@@ -54,6 +54,7 @@ typedef struct {
     int32_t mask_token_id, has_qkv_bias;
     int32_t wdtype;              /* 0: float32 arrays, 1: bf16 bit patterns (uint16) */
     double rope_theta, rms_eps, logit_scale;
+    int32_t bf16_points;         /* 1: round activations to bf16 at the points where a bf16 pipeline does (see round_rows) */
 } orc_cfg;
 
 typedef struct {
@@ -83,6 +84,32 @@ static double wget(const void *p, int wdtype, size_t i)
     float f;
     memcpy(&f, &bits, 4);
     return (double)f;
+}
+
+/*
+ * Optional model of a bf16 pipeline's rounding points.  The plain oracle (bf16_points = 0) keeps every
+ * intermediate in double.  With bf16_points = 1 the tensors that a bf16 matrix-core implementation has to hand to
+ * its contractions are rounded to bf16 (nearest even) where such an implementation rounds them: the output of
+ * every RMSNorm, the rotated queries and keys and the values, the softmax weights entering the weighted sum of
+ * values (their normaliser stays unrounded), the attention output, and the SwiGLU activation.  Nothing else
+ * changes.  This separates rounding noise, which no bf16 implementation can avoid, from errors.
+ */
+static double round_bf16(double v)
+{
+    float f = (float)v;
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return v;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    u &= 0xffff0000u;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+static void round_rows(const orc_cfg *c, double *x, size_t n)
+{
+    if (!c->bf16_points) return;
+    for (size_t i = 0; i < n; ++i) x[i] = round_bf16(x[i]);
 }
 
 /* y[r][o] = sum_k x[r][k] * W[o][k] (+ b[o]);  W is [n_out, n_in] row-major. */
@@ -156,6 +183,9 @@ static void qkv_rope(double *q, double *k, double *v, const double *xn, const or
         for (int hq = 0; hq < c->n_q_heads; ++hq) rope(q + (size_t)r * qd + hq * d, d, pos[r], c->rope_theta);
         for (int hk = 0; hk < c->n_kv_heads; ++hk) rope(k + (size_t)r * kd + hk * d, d, pos[r], c->rope_theta);
     }
+    round_rows(c, q, (size_t)rows * qd);
+    round_rows(c, k, (size_t)rows * kd);
+    round_rows(c, v, (size_t)rows * kd);
 }
 
 /* x += att * Wo ; x += (silu(xn Wg) * (xn Wu)) Wd   (second half of a decoder layer) */
@@ -169,9 +199,11 @@ static void out_and_ffn(double *x, const double *att, const orc_cfg *c, const or
     dense(t, att, w->wo[l], NULL, c->wdtype, rows, qd, h);
     for (size_t i = 0; i < (size_t)rows * h; ++i) x[i] += t[i];
     rmsnorm(xn, x, w->ffn_norm[l], c->wdtype, rows, h, c->rms_eps);
+    round_rows(c, xn, (size_t)rows * h);
     dense(g, xn, w->w_gate[l], NULL, c->wdtype, rows, h, F);
     dense(u, xn, w->w_up[l], NULL, c->wdtype, rows, h, F);
     for (size_t i = 0; i < (size_t)rows * F; ++i) g[i] = silu(g[i]) * u[i];
+    round_rows(c, g, (size_t)rows * F);
     dense(t, g, w->w_down[l], NULL, c->wdtype, rows, F, h);
     for (size_t i = 0; i < (size_t)rows * h; ++i) x[i] += t[i];
     free(t); free(xn); free(g); free(u);
@@ -183,6 +215,7 @@ static void lm_head(double *logits, const double *x, const orc_cfg *c, const orc
     int h = c->hidden, V = c->vocab;
     double *xn = malloc(sizeof(double) * (size_t)rows * h);
     rmsnorm(xn, x, w->final_norm, c->wdtype, rows, h, c->rms_eps);
+    round_rows(c, xn, (size_t)rows * h);
     dense(logits, xn, w->lm_head, NULL, c->wdtype, rows, h, V);
     for (size_t i = 0; i < (size_t)rows * V; ++i) logits[i] *= c->logit_scale;
     free(xn);
@@ -277,6 +310,7 @@ static void forward_masked(double *x, const orc_cfg *c, const orc_weights *w,
     embed_rows(x, c, w, ids, T);
     for (int l = 0; l < c->n_layers; ++l) {
         rmsnorm(xn, x, w->attn_norm[l], c->wdtype, T, h, c->rms_eps);
+        round_rows(c, xn, (size_t)T * h);
         qkv_rope(q, k, v, xn, c, w, l, T, pos);
 #pragma omp parallel for schedule(dynamic)
         for (int u = 0; u < T; ++u) {
@@ -300,13 +334,14 @@ static void forward_masked(double *x, const orc_cfg *c, const orc_weights *w,
                 for (int i = 0; i < d; ++i) o[i] = 0.0;
                 for (int t = 0; t < T; ++t) {
                     if (!mask[(size_t)u * T + t]) continue;
-                    double p = exp(sc[t] - m) / den;
+                    double p = (c->bf16_points ? round_bf16(exp(sc[t] - m)) : exp(sc[t] - m)) / den;
                     const double *vt = v + (size_t)t * kd + hk * d;
                     for (int i = 0; i < d; ++i) o[i] += p * vt[i];
                 }
             }
             free(sc);
         }
+        round_rows(c, att, (size_t)T * qd);
         out_and_ffn(x, att, c, w, l, T);
     }
     free(xn); free(q); free(k); free(v); free(att); free(pos);
@@ -374,6 +409,7 @@ int orc_ntp_logits(const orc_cfg *c, const orc_weights *w, const int32_t *tokens
     embed_rows(x, c, w, tokens, n);
     for (int l = 0; l < c->n_layers; ++l) {
         rmsnorm(xn, x, w->attn_norm[l], c->wdtype, n, h, c->rms_eps);
+        round_rows(c, xn, (size_t)n * h);
         qkv_rope(q, k, v, xn, c, w, l, n, pos);
         for (int u = 0; u < n; ++u)
             for (int hq = 0; hq < Hq; ++hq) {
@@ -388,10 +424,12 @@ int orc_ntp_logits(const orc_cfg *c, const orc_weights *w, const int32_t *tokens
                 for (int t = 0; t <= u; ++t) den += exp(sc[t] - m);
                 for (int i = 0; i < d; ++i) {
                     double o = 0.0;
-                    for (int t = 0; t <= u; ++t) o += exp(sc[t] - m) / den * v[(size_t)t * kd + hk * d + i];
+                    for (int t = 0; t <= u; ++t)
+                        o += (c->bf16_points ? round_bf16(exp(sc[t] - m)) : exp(sc[t] - m)) / den * v[(size_t)t * kd + hk * d + i];
                     att[(size_t)u * qd + hq * d + i] = o;
                 }
             }
+        round_rows(c, att, (size_t)n * qd);
         out_and_ffn(x, att, c, w, l, n);
     }
     lm_head(logits, x + (size_t)(n - 1) * h, c, w, 1);
@@ -470,6 +508,7 @@ static int seq_forward(orc_seq *s, int n_block, double *logits_out)
     for (int l = 0; l < c->n_layers; ++l) {
         double *Kc = s->K + (size_t)l * s->max_len * kd, *Vc = s->V + (size_t)l * s->max_len * kd;
         rmsnorm(xn, x, w->attn_norm[l], c->wdtype, R, h, c->rms_eps);
+        round_rows(c, xn, (size_t)R * h);
         qkv_rope(q, k, v, xn, c, w, l, R, pos);
         /* pending rows: their K/V are final; place them in the cache */
         for (int r = 0; r < p; ++r) {
@@ -502,12 +541,13 @@ static int seq_forward(orc_seq *s, int n_block, double *logits_out)
                 for (int t = 0; t < n_keys; ++t) {
                     const double *vt = t < n_cache ? Vc + (size_t)t * kd + hk * d
                                                    : v + (size_t)(p + t - n_cache) * kd + hk * d;
-                    double pr = exp(sc[t] - m) / den;
+                    double pr = (c->bf16_points ? round_bf16(exp(sc[t] - m)) : exp(sc[t] - m)) / den;
                     for (int i = 0; i < d; ++i) o[i] += pr * vt[i];
                 }
             }
             free(sc);
         }
+        round_rows(c, att, (size_t)R * qd);
         out_and_ffn(x, att, c, w, l, R);
     }
     if (n_block > 0 && logits_out) lm_head(logits_out, x + (size_t)p * h, c, w, n_block);
@@ -585,6 +625,13 @@ double orc_probe_logit(const orc_cfg *c, const orc_weights *w, const double *xha
     return acc * c->logit_scale;
 }
 
+/* All logits of one row: logit_scale * W_lm xhat. */
+void orc_probe_logits_row(const orc_cfg *c, const orc_weights *w, const double *xhat, double *out)
+{
+    dense(out, xhat, w->lm_head, NULL, c->wdtype, 1, c->hidden, c->vocab);
+    for (int v = 0; v < c->vocab; ++v) out[v] *= c->logit_scale;
+}
+
 /* One output feature of a linear layer: <x, W[o]> (+ b[o]). */
 double orc_probe_linear(const void *W, const void *b, int32_t wdtype, const double *x, int32_t n_in, int32_t o)
 {
@@ -617,3 +664,4 @@ void orc_probe_rmsnorm(const double *x, const void *g, int32_t wdtype, int32_t h
 
 void orc_probe_rope(double *v, int32_t d, int32_t pos, double theta) { rope(v, d, pos, theta); }
 double orc_probe_silu(double x) { return silu(x); }
+double orc_probe_round_bf16(double x) { return round_bf16(x); }

@@ -425,7 +425,9 @@ __global__ void read_kv_k(const T *pool, KvGeom kg, SeqState st, int seq, int kv
     int d = kg.head_dim;
     for (int e = blockIdx.x * blockDim.x + threadIdx.x; e < count * d; e += gridDim.x * blockDim.x) {
         int pos = pos0 + e / d, i = e % d;
-        int page = st.page_table[(size_t)seq * kg.pages_per_seq + pos / PAGE], slot = pos % PAGE;
+        int page, slot;
+        if (pos0 < 0) { page = kg.staging_base + seq; slot = e / d; }   // the block rows' staging tile
+        else { page = st.page_table[(size_t)seq * kg.pages_per_seq + pos / PAGE]; slot = pos % PAGE; }
         const T *Kb = pool + kg.tile(page, kvh), *Vb = Kb + PAGE * d;
         k_out[e] = to_f<T>(Kb[k_off(slot, i)]);
         v_out[e] = to_f<T>(Vb[v_off(slot, i)]);

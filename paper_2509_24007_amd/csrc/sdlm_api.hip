@@ -243,6 +243,7 @@ void run_layers(sdlm_ctx *c, int rows, int groups)
             GemmArgs a{c->att, w.wo, nullptr, nullptr, c->x, nullptr, c->rm.counts, rows, h, nq, 1.f};
             if (c->L.mfma) launch_gemm_mfma(s, EPI_RESID, a, c->slabs, c->L.slab_floats); else launch_gemm_generic(s, dt, EPI_RESID, a);
         }
+        run_taps(c, l, 6, c->x, (size_t)rows * h * 4);
         { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xn, c->x, w.ffn_norm, h, m.rms_eps, nullptr, c->rm.counts, rows); }
         {
             Phase p(c, SDLM_PH_GATEUP);
@@ -578,7 +579,7 @@ int sdlm_debug_tap(sdlm_ctx *c, int32_t layer, int32_t which, void *dst)
 {
     if (!c) return SDLM_EINVAL;
     if (which < 0) { c->taps.clear(); return SDLM_OK; }
-    if (which > 5 || !dst || (which != 4 && (layer < 0 || layer >= c->m.n_layers))) return fail(c, SDLM_EINVAL, "bad tap");
+    if (which > 6 || !dst || (which != 4 && (layer < 0 || layer >= c->m.n_layers))) return fail(c, SDLM_EINVAL, "bad tap");
     c->taps.push_back(Tap{layer, which, dst});
     return SDLM_OK;
 }
@@ -598,10 +599,13 @@ int sdlm_debug_rows(sdlm_ctx *c, int32_t *tok, int32_t *pos, int32_t *seq, int32
 int sdlm_debug_read_kv(sdlm_ctx *c, int32_t layer, int32_t seq, int32_t kv_head, int32_t pos0, int32_t count, float *k_out, float *v_out)
 {
     if (!c || !k_out || !v_out) return SDLM_EINVAL;
-    if (layer < 0 || layer >= c->m.n_layers || seq < 0 || seq >= c->batch || kv_head < 0 || kv_head >= c->m.n_kv_heads ||
-        pos0 < 0 || count < 1 || pos0 + count > c->r.max_seq_len)
+    if (layer < 0 || layer >= c->m.n_layers || seq < 0 || seq >= c->batch || kv_head < 0 || kv_head >= c->m.n_kv_heads || count < 1)
         return fail(c, SDLM_EINVAL, "read_kv arguments out of range");
-    if (c->r.kv_layout == 1) {   // positions must be backed: check against the exact lengths
+    if (pos0 == -1) {
+        if (count > c->r.block_D) return fail(c, SDLM_EINVAL, "the staging tile holds D entries");
+    } else if (pos0 < 0 || pos0 + count > c->r.max_seq_len) {
+        return fail(c, SDLM_EINVAL, "read_kv arguments out of range");
+    } else if (c->r.kv_layout == 1) {   // positions must be backed: check against the exact lengths
         int rc = refresh_lengths(c, nullptr);
         if (rc) return rc;
         if (pos0 + count > c->n_ub[seq]) return fail(c, SDLM_EINVAL, "positions beyond the sequence");

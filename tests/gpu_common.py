@@ -18,10 +18,14 @@ def gpu_context(mcfg, g_dev, layers_dev, *, max_batch, max_seq_len, D, tau, page
     return ctx
 
 
-def both_models(mcfg, seed, std):
-    """Weights generated once on the CPU (for the oracle) and moved to the GPU unchanged."""
+def both_models(mcfg, seed, std, rounded=False):
+    """Weights generated once on the CPU (for the oracle) and moved to the GPU unchanged.
+
+    rounded=True returns (oracle with the bf16 rounding-point model, exact oracle) in place of the exact oracle."""
     g, layers = make_model(mcfg, seed=seed, std=std)
     om = oracle_model(mcfg, g, layers)
+    if rounded:
+        om = (orc.model_from_inputs(mcfg, g, layers, bf16_points=True), om)
     g_dev = {k: v.cuda() for k, v in g.items()}
     layers_dev = [{k: (v.cuda() if v is not None else None) for k, v in L.items()} for L in layers]
     return om, g_dev, layers_dev
@@ -32,25 +36,37 @@ class Stats:
         self.rows = self.id_near_tie = self.gamma_near_tie = 0
         self.max_logit_err = self.max_conf_err = 0.0
         self.gammas = []
+        self.exact_errs = []
+        self.row_errs = []
 
     def __repr__(self):
         return (f"rows={self.rows} max_logit_rel_err={self.max_logit_err:.3e} max_conf_err={self.max_conf_err:.3e} "
-                f"id_near_tie={self.id_near_tie} gamma_near_tie={self.gamma_near_tie} mean_gamma={np.mean(self.gammas):.2f}")
+                + (f"median_logit_rel_err={np.median(self.row_errs):.3e} p90={np.quantile(self.row_errs, 0.9):.3e} " if self.row_errs else "") +
+                f"id_near_tie={self.id_near_tie} gamma_near_tie={self.gamma_near_tie} mean_gamma={np.mean(self.gammas):.2f}"
+                + (f" vs_exact_oracle[max={np.max(self.exact_errs):.3e} median={np.median(self.exact_errs):.3e} "
+                   f"p90={np.quantile(self.exact_errs, 0.9):.3e}]" if self.exact_errs else ""))
 
 
 def lockstep(ctx, om, prompts, D, tau, steps, *, logit_tol, conf_tol, conf_fn=0, rule=0, overrides=None,
-             tie_gap=1e-3, bf16=False, check_logits=True, max_len=None):
+             tie_gap=1e-3, bf16=False, check_logits=True, max_len=None, om_exact=None, exact_tol=2e-2):
     """Run the HIP library and one oracle sequence per prompt step by step on the same token history.
 
     After every step both sides commit the same tokens: the seeded override tokens on steps where `overrides`
     supplies them, otherwise the oracle's own accepted prefix (through the library's NULL commit when the two
     agree, through the override arguments otherwise).  Returns Stats; asserts the parity bar.
+
+    `om` may be the oracle with the bf16 rounding-point model switched on; `om_exact`, if given, is the plain
+    fp64 oracle run alongside on the same tokens: the library's logits must also stay within `exact_tol`
+    (row-normalised) of it.
     """
     B = len(prompts)
     V = om.vocab
     max_len = max_len or max(len(p) for p in prompts) + steps * D + D
     seqs = [orc.Seq(om, max_len) for _ in range(B)]
     for s, p in zip(seqs, prompts):
+        s.prefill(np.asarray(p))
+    seqs_x = [orc.Seq(om_exact, max_len) for _ in range(B)] if om_exact is not None else []
+    for s, p in zip(seqs_x, prompts):
         s.prefill(np.asarray(p))
     ctx.prefill(prompts)
     ids = torch.empty(B, D, dtype=torch.int32, device="cuda")
@@ -77,6 +93,7 @@ def lockstep(ctx, om, prompts, D, tau, steps, *, logit_tol, conf_tol, conf_fn=0,
                 if check_logits:
                     err_abs = float(np.max(np.abs(g_log[b, k] - lo[k])))
                     st.max_logit_err = max(st.max_logit_err, err_abs / zmax)
+                    st.row_errs.append(err_abs / zmax)
                     assert err_abs / zmax <= logit_tol, f"step {t} seq {b} row {k}: logit rel err {err_abs / zmax:.3e}"
                 band = max(tie_gap, 2.0 * err_abs) if bf16 else tie_gap
                 if g_ids[b, k] != io[k]:
@@ -99,6 +116,12 @@ def lockstep(ctx, om, prompts, D, tau, steps, *, logit_tol, conf_tol, conf_fn=0,
                 st.gamma_near_tie += 1
                 agree = False
             st.gammas.append(go)
+            if seqs_x and check_logits:
+                lx, _, _, _ = seqs_x[b].step(D, tau, rule, conf_fn)
+                for k in range(D):
+                    e = float(np.max(np.abs(g_log[b, k] - lx[k])) / np.max(np.abs(lx[k])))
+                    st.exact_errs.append(e)
+                    assert e <= exact_tol, f"step {t} seq {b} row {k}: {e:.3e} from the exact oracle (> {exact_tol})"
         if overrides is not None and t < overrides[0].shape[0] and t % 2 == 1:
             c_ids, c_cnt = overrides[0][t, :B].numpy().astype(np.int32), overrides[1][t, :B].numpy().astype(np.int32)
             use_null = False
@@ -111,6 +134,8 @@ def lockstep(ctx, om, prompts, D, tau, steps, *, logit_tol, conf_tol, conf_fn=0,
             ctx.kv_commit(torch.tensor(c_ids, dtype=torch.int32).cuda().contiguous(), torch.tensor(c_cnt, dtype=torch.int32).cuda())
         for b in range(B):
             assert seqs[b].commit(c_ids[b], int(c_cnt[b])) == 0
+            if seqs_x:
+                assert seqs_x[b].commit(c_ids[b], int(c_cnt[b])) == 0
         n, c = ctx.get_lengths()
         assert [int(v) for v in n] == [s.n for s in seqs] and [int(v) for v in c] == [s.c for s in seqs]
     return st, seqs

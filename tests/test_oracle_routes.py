@@ -152,3 +152,29 @@ def test_entropy_rule_runs_through_step(model):
         assert abs(conf[k] - np.float32(orc.conf_entropy(l[k]))) < 1e-7
         assert 0.0 <= conf[k] <= 1.0
     assert g == orc.gamma(conf, 0.01)
+
+
+def test_bf16_rounding_points_model():
+    """The optional rounding-point model: same three-way agreement, bf16-sized distance from the exact oracle."""
+    import torch
+    from helpers import make_model, oracle_model, small_cfg
+    for x in (1.0, 1.00390625, 1.005859375, -3.14159, 1e-3, 65504.0, 0.1):
+        want = float(torch.tensor(x, dtype=torch.float32).to(torch.bfloat16).to(torch.float32))
+        assert orc.probe_round_bf16(x) == want
+    assert orc.probe_round_bf16(1.0 + 2.0 ** -8) == 1.0            # tie to even
+    assert orc.probe_round_bf16(1.0 + 3 * 2.0 ** -8) == 1.0 + 2.0 ** -6
+    m = small_cfg(dtype="bf16")
+    g, layers = make_model(m, seed=11, std=0.3)
+    exact = oracle_model(m, g, layers)
+    rounded = orc.model_from_inputs(m, g, layers, bf16_points=True)
+    prompt = syn.uniform_int(3, "r", 9, 0, m.vocab - 1).numpy()
+    le, _, _, _ = orc.brute_step(exact, prompt, 4, 0.5)
+    lr, ir, cr, gr = orc.brute_step(rounded, prompt, 4, 0.5)
+    assert 1e-5 < rel_err(lr, le) < 5e-2
+    seq = orc.Seq(rounded, 64)
+    seq.prefill(prompt)
+    lc, ic, cc, gc = seq.step(4, 0.5)
+    assert rel_err(lc, lr) < 1e-9 and gc == gr
+    assert rel_err(orc.ntp_logits(rounded, prompt), orc.brute_step(rounded, prompt, 1, 0.5)[0][0]) < 1e-9
+    k, v = seq.read_kv(0, 3, 1)
+    assert all(orc.probe_round_bf16(float(t)) == float(t) for t in k) and all(orc.probe_round_bf16(float(t)) == float(t) for t in v)
