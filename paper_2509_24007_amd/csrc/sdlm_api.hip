@@ -340,6 +340,9 @@ int sdlm_create(const sdlm_model_cfg *m, const sdlm_run_cfg *r, void *workspace,
         for (int p = 0; p < max_pos; ++p) tab[(size_t)p * half + i] = make_float2((float)cos(p * w), (float)sin(p * w));
     }
     HIPCHK(c, hipMemcpyAsync(c->rope, tab.data(), tab.size() * sizeof(float2), hipMemcpyHostToDevice, c->stream));
+    // The K/V pool starts at zero: masked keys contribute weight 0 to the weighted sum of values, and 0 times a stale
+    // non-finite bit pattern would not be 0.  Slots are only ever overwritten with finite K/V afterwards.
+    HIPCHK(c, hipMemsetAsync(c->pool, 0, (size_t)m->n_layers * c->kg.layer_stride * L.esz, c->stream));
     HIPCHK(c, hipMemsetAsync(ws + L.state_i32, 0, L.state_ints * 4, c->stream));
     HIPCHK(c, hipMemsetAsync(ws + L.meta_i32, 0, L.meta_ints * 4, c->stream));
     HIPCHK(c, hipStreamSynchronize(c->stream));

@@ -117,7 +117,7 @@ class Context:
 
     def __init__(self, mcfg: ModelCfg, *, max_batch: int, max_seq_len: int, block_D: int, tau: float,
                  paged: bool = False, n_pages: int = 0, conf_fn: int = 0, accept_rule: int = 0,
-                 prefill_rows: int = 0, device="cuda:0"):
+                 prefill_rows: int = 0, device="cuda:0", poison: bool = False):
         L = load()
         self.L = L
         self.m = mcfg
@@ -134,6 +134,8 @@ class Context:
             raise SdlmError(rc, msg)
         self.workspace_bytes = need
         self.workspace = torch.empty(need + 256, dtype=torch.uint8, device=self.device)
+        if poison:   # tests: every byte 0xFF (NaN as bf16/fp32, -1 as int) so that reliance on fresh memory shows
+            self.workspace.fill_(0xFF)
         base = self.workspace.data_ptr()
         self._ws_ptr = (base + 255) // 256 * 256
         self.stream = torch.cuda.current_stream(self.device)

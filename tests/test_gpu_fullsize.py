@@ -60,7 +60,8 @@ def test_fullsize_stagewise(name):
     steps = 3
     max_len = max(len(p) for p in prompts) + steps * D + D
     n_pages = sum((len(p) + steps * D + D + 15) // 16 + 1 for p in prompts) if r.paged else 0
-    ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=B, max_seq_len=max_len, block_D=D, tau=tau, paged=r.paged, n_pages=n_pages)
+    ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=B, max_seq_len=max_len, block_D=D, tau=tau, paged=r.paged, n_pages=n_pages,
+                       poison=True)
     assert ctx.kernel_info == "mfma-bf16"
     layers_checked = (0, m.n_layers - 1)
     host_g, host_layers = load_streaming(ctx, m, wl.seed, keep=layers_checked)
@@ -209,7 +210,7 @@ def test_c2_bf16_whole_path():
     D, tau = r.block_D, r.tau
     prompt = syn.make_prompts(wl.seed, 1, r.prompt_lo, r.prompt_hi, m.vocab)[0].numpy()
     max_len = len(prompt) + r.steps * D + D
-    ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=1, max_seq_len=max_len, block_D=D, tau=tau)
+    ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=1, max_seq_len=max_len, block_D=D, tau=tau, poison=True)
     g = syn.make_globals(m, wl.seed, device="cuda")
     layers = [syn.make_layer(m, wl.seed, l, device="cuda") for l in range(m.n_layers)]
     ctx.init_weights(g, {l: layers[l] for l in range(m.n_layers)})
@@ -248,7 +249,7 @@ def test_c2_shape_fp32_debug_mode():
     m = syn.ModelCfg(**{**wl.model.__dict__, "dtype": "fp32"})
     D, tau = 4, 0.9
     prompt = syn.make_prompts(wl.seed, 1, 48, 48, m.vocab)[0].numpy()
-    ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=1, max_seq_len=96, block_D=D, tau=tau, prefill_rows=64)
+    ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=1, max_seq_len=96, block_D=D, tau=tau, prefill_rows=64, poison=True)
     g = syn.make_globals(m, wl.seed, device="cuda")
     layers = [syn.make_layer(m, wl.seed, l, device="cuda") for l in range(m.n_layers)]
     ctx.init_weights(g, {l: layers[l] for l in range(m.n_layers)})
