@@ -77,7 +77,8 @@ template <int MT, int NT, int EPI>
 __global__ __launch_bounds__(256) void gemm_mfma_k(MfmaArgs a)
 {
     __shared__ __attribute__((aligned(16))) bf16_t Xs[2][MT * 32][XS_STRIDE];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps the weight stream's base in SGPRs
     const int R = min(*a.pR, a.max_rows);
     // workgroup id -> tile: ids that land on one XCD (id % 8) get consecutive tiles
     const int per = gridDim.x >> 3;
@@ -90,19 +91,22 @@ __global__ __launch_bounds__(256) void gemm_mfma_k(MfmaArgs a)
     const int s_begin = split * a.stages_per_split, s_end = min(S, s_begin + a.stages_per_split);
     if (s_begin >= s_end) return;
 
+    // Addresses are (wave-uniform base) + (32-bit per-lane offset): the loads then take their base from SGPRs and
+    // no address register is ever the destination of a load still in flight.
     const bf16_t *wp[NT];
     int ntile[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         ntile[nt] = (nblk * 4 + wave) * NT + nt;
         int tl = min(ntile[nt], a.n_tiles - 1);
-        wp[nt] = a.Wp + ((size_t)tl * KS) * 512 + lane * 8;
+        wp[nt] = a.Wp + ((size_t)tl * KS) * 512;
     }
+    const uint32_t wlane = lane * 8;
     // activation slice: MT*32 rows x 64 k = MT*256 16-byte chunks, MT per thread
     const int xrow = tid >> 3, xchunk = tid & 7;
-    const bf16_t *xp[MT];
+    uint32_t xoff[MT];
 #pragma unroll
-    for (int i = 0; i < MT; ++i) xp[i] = a.X + (size_t)min(m0 + i * 32 + xrow, R - 1) * a.K + xchunk * 8;
+    for (int i = 0; i < MT; ++i) xoff[i] = (uint32_t)min(m0 + i * 32 + xrow, R - 1) * (uint32_t)a.K + xchunk * 8;
 
     f32x16 acc[NT][MT];
 #pragma unroll
@@ -124,12 +128,12 @@ __global__ __launch_bounds__(256) void gemm_mfma_k(MfmaArgs a)
     {                                                                                                             \
         const size_t so_ = (size_t)min((stage), s_last) * 4 * 512;                                                \
         _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                        \
-            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) dst[nt][ks] = *(const bf16x8 *)(wp[nt] + so_ + ks * 512); \
+            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) dst[nt][ks] = *(const bf16x8 *)(wp[nt] + so_ + ks * 512 + wlane); \
     }
 #define SDLM_LOAD_X(stage)                                                                                        \
     {                                                                                                             \
         const size_t xo_ = (size_t)min((stage), s_last) * 64;                                                     \
-        _Pragma("unroll") for (int i = 0; i < MT; ++i) xr[i] = *(const u32x4 *)(xp[i] + xo_);                    \
+        _Pragma("unroll") for (int i = 0; i < MT; ++i) xr[i] = *(const u32x4 *)(a.X + xo_ + xoff[i]);                    \
     }
     SDLM_LOAD_X(s_begin);
     SDLM_LOAD_W(w0, s_begin);
@@ -155,7 +159,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_k(MfmaArgs a)
         _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) bc_[mt] = bn_[mt];                                     \
     }
 #define SDLM_STAGE(WC, WN, stage)                                                                                 \
-    if ((stage) < s_end) {                                                                                        \
+    {                                                                                                             \
         SDLM_LOAD_X((stage) + 1);                                                                                 \
         SDLM_LOAD_W(WN, (stage) + 2);                                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                                        \
@@ -168,10 +172,17 @@ __global__ __launch_bounds__(256) void gemm_mfma_k(MfmaArgs a)
         buf ^= 1;                                                                                                 \
         __syncthreads();                                                                                          \
     }
-    for (int s = s_begin; s < s_end; s += 3) {
+    // Full triples run without any branch inside the loop (a conditional stage would make the compiler drain all
+    // outstanding loads at the loop head); the 0..2 remaining slices are peeled.
+    int s = s_begin;
+    for (; s + 3 <= s_end; s += 3) {
         SDLM_STAGE(w0, w2, s)
         SDLM_STAGE(w1, w0, s + 1)
         SDLM_STAGE(w2, w1, s + 2)
+    }
+    if (s < s_end) {
+        SDLM_STAGE(w0, w2, s)
+        if (s + 1 < s_end) SDLM_STAGE(w1, w0, s + 1)
     }
 #undef SDLM_STAGE
 #undef SDLM_KSTEP
