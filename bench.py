@@ -32,6 +32,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="also time the other thresholds of the workload's tau sweep")
     ap.add_argument("--profile-all", action="store_true", help="bracket every phase with events (adds overhead)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run one plain 1 GiB device copy first: under rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE give the counter scale")
     return ap.parse_args()
 
 
@@ -122,6 +124,14 @@ def main():
     from paper_2509_24007_amd import inputs as syn
     from paper_2509_24007_amd import sdlm
 
+    if a.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read, 1 GiB written
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     wl = syn.workloads()[a.config]
     m, r = wl.model, wl.run
     tau = a.tau if a.tau is not None else r.tau

@@ -201,35 +201,48 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
     if (!single && lg == 0) a.part_ml[item * QMAX + qi] = make_float2(m_run, l_run);
 }
 
-// Merge the chunks of one (group, kv head): out = sum_c 2^{m_c - M} o_c / sum_c 2^{m_c - M} l_c.
+// Merge the chunks of one (group, kv head): out = sum_c 2^{c(m_c - M)} o_c / sum_c 2^{c(m_c - M)} l_c.  A separate
+// launch rather than "the last workgroup merges": the chunks run on different XCDs, whose L2s only agree at
+// kernel boundaries, and a device-scope fence in every workgroup costs more than this launch.
+// grid (group, kv head, 16-query tile); the tile's scale factors are computed once and shared through LDS.
 __global__ __launch_bounds__(256) void attn_combine_k(AttnArgs a)
 {
-    const int g = blockIdx.x, hk = blockIdx.y;
+    const int g = blockIdx.x, hk = blockIdx.y, nq = blockIdx.z;
     if (g >= a.rm.counts[1]) return;
     const int row0 = a.rm.grp_row0[g], nrows = a.rm.grp_n[g];
     const int QR = nrows * a.G;
+    if (nq * 16 >= QR) return;
     int lim = 0;
     for (int i = 0; i < nrows; ++i) lim = max(lim, a.rm.lim[row0 + i]);
     const int n_pages = (lim + PAGE - 1) / PAGE;
     const int n_chunks = max(1, (n_pages + a.chunk_pages - 1) / a.chunk_pages);
     if (n_chunks == 1) return;   // the attention kernel wrote the final result itself
     const size_t item0 = ((size_t)g * a.kg.n_kv_heads + hk) * a.max_chunks;
-    for (int e = threadIdx.x; e < QR * (HD / 4); e += 256) {
-        int qi = e / (HD / 4), d4 = (e % (HD / 4)) * 4;
+    __shared__ float sf[16][65];   // [query][chunk]: 2^{c(m_c - M)} / L
+    const int tid = threadIdx.x;
+    if (tid < 16 && nq * 16 + tid < QR) {
+        const int qi = nq * 16 + tid;
         float M = -INFINITY;
         for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, a.part_ml[(item0 + c) * QMAX + qi].x);
         float L = 0.f;
-        f32x4 o = {0.f, 0.f, 0.f, 0.f};
         for (int c = 0; c < n_chunks; ++c) {
             float2 ml = a.part_ml[(item0 + c) * QMAX + qi];
             float f = ml.x == -INFINITY ? 0.f : exp2f((ml.x - M) * a.c);
+            sf[tid][c] = f;
             L += ml.y * f;
-            o += *(const f32x4 *)(a.part_o + ((item0 + c) * QMAX + qi) * HD + d4) * f;
         }
-        float inv = 1.0f / L;
-        int rl = qi / a.G, hg = qi % a.G;
+        const float inv = 1.0f / L;
+        for (int c = 0; c < n_chunks; ++c) sf[tid][c] *= inv;
+    }
+    __syncthreads();
+    for (int e = tid; e < 16 * (HD / 4); e += 256) {
+        const int ql = e / (HD / 4), d4 = (e % (HD / 4)) * 4, qi = nq * 16 + ql;
+        if (qi >= QR) continue;
+        f32x4 o = {0.f, 0.f, 0.f, 0.f};
+        for (int c = 0; c < n_chunks; ++c) o += *(const f32x4 *)(a.part_o + ((item0 + c) * QMAX + qi) * HD + d4) * sf[ql][c];
+        const int rl = qi / a.G, hg = qi % a.G;
         bf16_t *op = a.out + ((size_t)(row0 + rl) * a.Hq + hk * a.G + hg) * HD + d4;
-        *(uint2 *)op = make_uint2(pack_bf16(o[0] * inv, o[1] * inv), pack_bf16(o[2] * inv, o[3] * inv));
+        *(uint2 *)op = make_uint2(pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3]));
     }
 }
 
@@ -247,6 +260,7 @@ static void chunking(const sdlm_model_cfg *m, int max_seq_len, int groups, int *
     long items = (long)groups * m->n_kv_heads;
     int cp = 64;                                     // 1024 keys
     while (cp > 8 && items * ((pages + cp - 1) / cp) < 512) cp >>= 1;
+    while ((pages + cp - 1) / cp > 64) cp <<= 1;     // the merge kernel keeps at most 64 scale factors per query
     *chunk_pages = cp;
     *max_chunks = (pages + cp - 1) / cp;
 }
@@ -287,7 +301,7 @@ void launch_attn_mfma(hipStream_t s, const sdlm_model_cfg *m, int max_seq_len, c
     a.c = 1.4426950408889634f / sqrtf((float)HD);
     hipLaunchKernelGGL(attn_mfma_k, dim3(max_groups, kg.n_kv_heads, a.max_chunks), dim3(256), 0, s, a);
     if (a.max_chunks > 1)
-        hipLaunchKernelGGL(attn_combine_k, dim3(max_groups, kg.n_kv_heads), dim3(256), 0, s, a);
+        hipLaunchKernelGGL(attn_combine_k, dim3(max_groups, kg.n_kv_heads, NQ), dim3(256), 0, s, a);
 }
 
 }  // namespace sdlm

@@ -98,8 +98,8 @@ struct GemmArgs {
 
 void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows);
 void launch_embed(hipStream_t s, int dtype, float *x, const void *E, const RowMeta &rm, int max_rows, int h, int V);
-void launch_rmsnorm(hipStream_t s, int dtype, void *out, const float *x, const void *g, int h, float eps,
-                    const int32_t *row_index, const int32_t *p_count, int max_rows);
+void launch_rmsnorm(hipStream_t s, int dtype, void *out, float *x, const void *g, int h, float eps, const int32_t *row_index,
+                    const int32_t *p_count, int max_rows, const float *slabs, int n_slabs, size_t slab_stride);
 void launch_gemm_generic(hipStream_t s, int dtype, int epi, const GemmArgs &a);
 void launch_rope_scatter(hipStream_t s, int dtype, const float *qkv, int n_slabs, size_t slab_stride, void *q_out, void *pool_layer,
                          const KvGeom &kg, const RowMeta &rm, const SeqState &st, const float2 *rope, int n_q_heads, int max_rows);

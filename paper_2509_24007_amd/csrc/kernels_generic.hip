@@ -79,27 +79,46 @@ __device__ inline float block_sum(float v, float *red)
     return t;
 }
 
-// out[j,:] = x[row,:] * g / sqrt(mean(x[row,:]^2) + eps), row = row_index ? row_index[j] : j
+// out[j,:] = x[row,:] * g / sqrt(mean(x[row,:]^2) + eps), row = row_index ? row_index[j] : j.  When the projection
+// that produced the residual update was split along k, its partial sums (n_slabs slabs of [rows, h]) are first added
+// to x[row,:] in slab order and written back, so the residual stream is complete after this kernel.
 template <typename T>
-__global__ __launch_bounds__(256) void rmsnorm_k(T *out, const float *x, const T *g, int h, float eps,
-                                                 const int32_t *row_index, const int32_t *p_count)
+__global__ __launch_bounds__(256) void rmsnorm_k(T *out, float *x, const T *g, int h, float eps, const int32_t *row_index,
+                                                 const int32_t *p_count, const float *slabs, int n_slabs, size_t slab_stride)
 {
     __shared__ float red[4];
     int j = blockIdx.x;
     if (j >= *p_count) return;
-    const float *xr = x + (size_t)(row_index ? row_index[j] : j) * h;
+    const int row = row_index ? row_index[j] : j;
+    float *xr = x + (size_t)row * h;
     float ss = 0.f;
-    for (int k = threadIdx.x; k < h; k += 256) ss += xr[k] * xr[k];
+    for (int k = threadIdx.x * 4; k < h; k += 1024) {
+        float4 v = *(const float4 *)(xr + k);
+        if (n_slabs > 0) {
+            for (int sl = 0; sl < n_slabs; ++sl) {
+                float4 p = *(const float4 *)(slabs + sl * slab_stride + (size_t)row * h + k);
+                v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+            }
+            *(float4 *)(xr + k) = v;
+        }
+        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
     ss = block_sum(ss, red);
     float inv = 1.0f / sqrtf(ss / (float)h + eps);
-    for (int k = threadIdx.x; k < h; k += 256) out[(size_t)j * h + k] = from_f<T>(xr[k] * inv * to_f<T>(g[k]));
+    for (int k = threadIdx.x * 4; k < h; k += 1024) {
+        float4 v = *(const float4 *)(xr + k);   // this thread's own elements: written above by itself
+        T o[4] = {from_f<T>(v.x * inv * to_f<T>(g[k])), from_f<T>(v.y * inv * to_f<T>(g[k + 1])),
+                  from_f<T>(v.z * inv * to_f<T>(g[k + 2])), from_f<T>(v.w * inv * to_f<T>(g[k + 3]))};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) out[(size_t)j * h + k + e] = o[e];
+    }
 }
 
-void launch_rmsnorm(hipStream_t s, int dtype, void *out, const float *x, const void *g, int h, float eps,
-                    const int32_t *row_index, const int32_t *p_count, int max_rows)
+void launch_rmsnorm(hipStream_t s, int dtype, void *out, float *x, const void *g, int h, float eps, const int32_t *row_index,
+                    const int32_t *p_count, int max_rows, const float *slabs, int n_slabs, size_t slab_stride)
 {
-    if (dtype == 0) hipLaunchKernelGGL(rmsnorm_k<float>, dim3(max_rows), dim3(256), 0, s, (float *)out, x, (const float *)g, h, eps, row_index, p_count);
-    else hipLaunchKernelGGL(rmsnorm_k<bf16_t>, dim3(max_rows), dim3(256), 0, s, (bf16_t *)out, x, (const bf16_t *)g, h, eps, row_index, p_count);
+    if (dtype == 0) hipLaunchKernelGGL(rmsnorm_k<float>, dim3(max_rows), dim3(256), 0, s, (float *)out, x, (const float *)g, h, eps, row_index, p_count, slabs, n_slabs, slab_stride);
+    else hipLaunchKernelGGL(rmsnorm_k<bf16_t>, dim3(max_rows), dim3(256), 0, s, (bf16_t *)out, x, (const bf16_t *)g, h, eps, row_index, p_count, slabs, n_slabs, slab_stride);
 }
 
 // ------------------------------------------------------------------------------------------------ GEMM (FMA)

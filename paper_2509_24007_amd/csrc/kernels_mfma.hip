@@ -424,7 +424,7 @@ static void launch_cfg(hipStream_t s, const TileChoice &c, MfmaArgs &a)
 #undef SDLM_GO
 }
 
-int launch_gemm_mfma(hipStream_t s, int epi, const GemmArgs &g, float *slabs, size_t slab_room_floats)
+int launch_gemm_mfma(hipStream_t s, int epi, const GemmArgs &g, float *slabs, size_t slab_room_floats, bool defer_reduce)
 {
     MfmaArgs a{};
     a.X = (const bf16_t *)g.X; a.Wp = (const bf16_t *)g.W; a.bias = (const bf16_t *)g.bias;
@@ -439,9 +439,9 @@ int launch_gemm_mfma(hipStream_t s, int epi, const GemmArgs &g, float *slabs, si
     case EPI_RESID: launch_cfg<EPI_RESID>(s, c, a); break;
     default: launch_cfg<EPI_SWIGLU>(s, c, a); break;
     }
-    if (c.splits > 1 && epi == EPI_RESID)
+    if (c.splits > 1 && epi == EPI_RESID && !defer_reduce)
         hipLaunchKernelGGL(reduce_slabs_k, dim3(g.max_rows), dim3(256), 0, s, g.Yf, slabs, c.splits, a.slab, g.N, g.pR, g.max_rows);
-    return c.splits;   // for STORE_F32 the caller's consumer adds the slabs
+    return c.splits;   // slabs left for the consumer: always for STORE_F32, for RESID when defer_reduce
 }
 
 void launch_lmhead_mfma(hipStream_t s, const void *xhat, const void *w_packed, const int32_t *p_rows, int max_rows, int V, int h, float scale,

@@ -21,9 +21,10 @@ int mfma_group_rows(const sdlm_model_cfg *m);
 // dst_rows rows.  interleave: 0 plain; 1 / 2: the matrix is the gate / up half of the fused gate-up matrix,
 // whose 32-row tiles alternate gate, up.
 void launch_pack_mfma(hipStream_t s, void *dst, const void *src, int N, int K, int dst_row0, int dst_rows, int interleave);
-// Returns the number of split-k slabs written to `slabs` for EPI_STORE_F32 (1: the result is in a.Yf); EPI_RESID
-// results are always complete in a.Yf on return.
-int launch_gemm_mfma(hipStream_t s, int epi, const GemmArgs &a, float *slabs, size_t slab_room_floats);
+// Returns the number of split-k slabs written to `slabs` (1: the result is complete in a.Yf / a.Yt).  For
+// EPI_STORE_F32 the consumer always adds the slabs; for EPI_RESID the slabs are added to a.Yf here unless
+// defer_reduce, in which case the next RMSNorm adds them (slab stride = a.max_rows * a.N floats).
+int launch_gemm_mfma(hipStream_t s, int epi, const GemmArgs &a, float *slabs, size_t slab_room_floats, bool defer_reduce);
 void launch_attn_mfma(hipStream_t s, const sdlm_model_cfg *m, int max_seq_len, const void *q, void *out, const void *pool_layer,
                       const KvGeom &kg, const RowMeta &rm, const SeqState &st, int D, int max_groups, void *scratch, size_t scratch_bytes);
 void launch_lmhead_mfma(hipStream_t s, const void *xhat, const void *w_packed, const int32_t *p_rows, int max_rows, int V, int h,

@@ -146,6 +146,8 @@ struct sdlm_ctx {
     float *slabs;
     int32_t *ids_rows;
     int batch = 0;
+    int pend_slabs = 0;                  // split-k slabs of the last residual projection not yet added to x
+    size_t pend_stride = 0;
     bool prefilled = false, stepped = false;
     std::vector<int32_t> n_ub;           // host upper bound of n_b
     std::vector<Tap> taps;
@@ -215,17 +217,18 @@ void run_layers(sdlm_ctx *c, int rows, int groups)
     const int nq = m.n_q_heads * d, nk = m.n_kv_heads * d, nqkv = nq + 2 * nk;
     const size_t e = c->L.esz;
     hipStream_t s = c->stream;
+    c->pend_slabs = 0;   // a fresh residual stream: nothing pending from an earlier pass
     { Phase p(c, SDLM_PH_ROWS); launch_embed(s, dt, c->x, c->embed, c->rm, rows, h, m.vocab); }
     for (int l = 0; l < m.n_layers; ++l) {
         const LayerW &w = c->lw[l];
         char *pool_l = c->pool + (size_t)l * c->kg.layer_stride * e;
         run_taps(c, l, 0, c->x, (size_t)rows * h * 4);
-        { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xn, c->x, w.attn_norm, h, m.rms_eps, nullptr, c->rm.counts, rows); }
+        { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xn, c->x, w.attn_norm, h, m.rms_eps, nullptr, c->rm.counts, rows, c->slabs, c->pend_slabs, c->pend_stride); c->pend_slabs = 0; }
         int qkv_slabs = 1;
         {
             Phase p(c, SDLM_PH_QKV);
             GemmArgs a{c->xn, w.wqkv, nullptr, m.has_qkv_bias ? w.bqkv : nullptr, c->qkv, nullptr, c->rm.counts, rows, nqkv, h, 1.f};
-            if (c->L.mfma) qkv_slabs = launch_gemm_mfma(s, EPI_STORE_F32, a, c->slabs, c->L.slab_floats); else launch_gemm_generic(s, dt, EPI_STORE_F32, a);
+            if (c->L.mfma) qkv_slabs = launch_gemm_mfma(s, EPI_STORE_F32, a, c->slabs, c->L.slab_floats, false); else launch_gemm_generic(s, dt, EPI_STORE_F32, a);
         }
         {
             Phase p(c, SDLM_PH_ROPE);
@@ -241,20 +244,28 @@ void run_layers(sdlm_ctx *c, int rows, int groups)
         {
             Phase p(c, SDLM_PH_OPROJ);
             GemmArgs a{c->att, w.wo, nullptr, nullptr, c->x, nullptr, c->rm.counts, rows, h, nq, 1.f};
-            if (c->L.mfma) launch_gemm_mfma(s, EPI_RESID, a, c->slabs, c->L.slab_floats); else launch_gemm_generic(s, dt, EPI_RESID, a);
+            if (c->L.mfma) {
+                // the split-k partial sums of a residual projection are added by the next RMSNorm (unless a tap wants x now)
+                int sp = launch_gemm_mfma(s, EPI_RESID, a, c->slabs, c->L.slab_floats, c->taps.empty());
+                if (sp > 1 && c->taps.empty()) { c->pend_slabs = sp; c->pend_stride = (size_t)rows * h; }
+            } else launch_gemm_generic(s, dt, EPI_RESID, a);
         }
         run_taps(c, l, 6, c->x, (size_t)rows * h * 4);
-        { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xn, c->x, w.ffn_norm, h, m.rms_eps, nullptr, c->rm.counts, rows); }
+        { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xn, c->x, w.ffn_norm, h, m.rms_eps, nullptr, c->rm.counts, rows, c->slabs, c->pend_slabs, c->pend_stride); c->pend_slabs = 0; }
         {
             Phase p(c, SDLM_PH_GATEUP);
             GemmArgs a{c->xn, w.w_gate, w.w_up, nullptr, nullptr, c->act, c->rm.counts, rows, F, h, 1.f};
-            if (c->L.mfma) launch_gemm_mfma(s, EPI_SWIGLU, a, c->slabs, c->L.slab_floats); else launch_gemm_generic(s, dt, EPI_SWIGLU, a);
+            if (c->L.mfma) launch_gemm_mfma(s, EPI_SWIGLU, a, c->slabs, c->L.slab_floats, false); else launch_gemm_generic(s, dt, EPI_SWIGLU, a);
         }
         run_taps(c, l, 2, c->act, (size_t)rows * F * e);
         {
             Phase p(c, SDLM_PH_DOWN);
             GemmArgs a{c->act, w.w_down, nullptr, nullptr, c->x, nullptr, c->rm.counts, rows, h, F, 1.f};
-            if (c->L.mfma) launch_gemm_mfma(s, EPI_RESID, a, c->slabs, c->L.slab_floats); else launch_gemm_generic(s, dt, EPI_RESID, a);
+            if (c->L.mfma) {
+                // the split-k partial sums of a residual projection are added by the next RMSNorm (unless a tap wants x now)
+                int sp = launch_gemm_mfma(s, EPI_RESID, a, c->slabs, c->L.slab_floats, c->taps.empty());
+                if (sp > 1 && c->taps.empty()) { c->pend_slabs = sp; c->pend_stride = (size_t)rows * h; }
+            } else launch_gemm_generic(s, dt, EPI_RESID, a);
         }
         run_taps(c, l, 3, c->x, (size_t)rows * h * 4);
     }
@@ -517,7 +528,7 @@ int sdlm_decode_step(sdlm_ctx *c, int32_t *ids, int32_t *count, float *conf, flo
     { Phase p(c, SDLM_PH_ROWS); launch_assemble_decode(s, c->st, c->rm, B, D, c->m.mask_token_id, c->L.group_rows); }
     run_layers(c, rows, B * ((2 * D + c->L.group_rows - 1) / c->L.group_rows));
     const int dt = c->m.dtype, h = c->m.hidden, V = c->m.vocab;
-    { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xhat, c->x, c->final_norm, h, c->m.rms_eps, c->rm.blk_row, c->rm.counts + 2, B * D); }
+    { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xhat, c->x, c->final_norm, h, c->m.rms_eps, c->rm.blk_row, c->rm.counts + 2, B * D, c->slabs, c->pend_slabs, c->pend_stride); c->pend_slabs = 0; }
     run_taps(c, 0, 4, c->xhat, (size_t)B * D * h * c->L.esz);
     {
         Phase p(c, SDLM_PH_LMHEAD);
