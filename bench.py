@@ -22,6 +22,18 @@ PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
 PEAK_BF16_TFLOPS = 2500.0    # dense MFMA bf16
 
 
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload, if there is one
+    (lines "traffic_bytes_per_launch <workload> <kernel> <bytes>" in profiles/*.txt)."""
+    import glob
+    for f in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt"))):
+        for line in open(f):
+            t = line.split()
+            if len(t) == 4 and t[0] == "traffic_bytes_per_launch" and t[1] == workload and t[2] == kernel:
+                return float(t[3])
+    return None
+
+
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -92,20 +104,22 @@ def run_tau(ctx, m, r, prompts, tau_idx, steps, warmup, prof_phases):
     return t1 - t0, cnt.cpu(), phases, n
 
 
-def cpu_baseline(m, host_g, host_layers, prompt, D, tau, n_steps=2, prompt_tokens=8):
+def cpu_baseline(m, host_g, host_layers, prompt, D, tau, budget_s=12.0, max_steps=64, prompt_tokens=8):
+    """The oracle as it stands, timed on a bounded sample: decode steps of one sequence until about budget_s seconds."""
     from oracle import oracle as orc
     om = orc.model_from_inputs(m, host_g, host_layers)
-    seq = orc.Seq(om, prompt_tokens + n_steps * D + D)
+    seq = orc.Seq(om, prompt_tokens + max_steps * D + D)
     t0 = time.perf_counter()
     seq.prefill(prompt[:prompt_tokens])
     t_pre = time.perf_counter() - t0
-    acc, t_steps = 0, 0.0
-    for _ in range(n_steps):
+    acc, t_steps, n_steps = 0, 0.0, 0
+    while n_steps < max_steps and (n_steps < 2 or t_steps < budget_s):
         t0 = time.perf_counter()
         _, _, _, g = seq.step(D, tau, want_logits=False)
         seq.commit()
         t_steps += time.perf_counter() - t0
         acc += g
+        n_steps += 1
     return {"value": acc / t_steps, "unit": "accepted tokens/s", "cores": orc.num_threads(), "kind": "oracle",
             "sample": f"sequence 0 truncated to its first {prompt_tokens} prompt tokens, {n_steps} decode steps, all "
                       f"{m.n_layers} layers and the full vocabulary; the oracle decodes one sequence at a time, so its rate "
@@ -206,6 +220,7 @@ def main():
         else:
             roof = dict(kernel=dom, bound="mfma", achieved=t["tflops"], peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                         frac=t["tflops"] / PEAK_BF16_TFLOPS, traffic=None)
+        roof["traffic"] = measured_traffic(a.config, dom)
         roof["avg_launch_us"] = t["avg_us"]
         roof["launches"] = t["launches"]
     step_bytes = main_r["w_bytes"] + main_r["kv_bytes"]
@@ -238,9 +253,7 @@ def main():
     del ctx
     torch.cuda.empty_cache()
     if want_cpu:
-        steps_cpu = 2 if m.n_layers * m.hidden > 20000 else 8
-        out["cpu_baseline"] = cpu_baseline(m, host_g, host_layers, prompts[0], D, tau, n_steps=steps_cpu,
-                                           prompt_tokens=min(8, len(prompts[0])))
+        out["cpu_baseline"] = cpu_baseline(m, host_g, host_layers, prompts[0], D, tau, prompt_tokens=min(8, len(prompts[0])))
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out))
