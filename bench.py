@@ -22,6 +22,9 @@ PEAK_HBM_GBS = 8000.0        # MI355X HBM3E
 PEAK_BF16_TFLOPS = 2500.0    # dense MFMA bf16
 
 
+MAIN_PHASES = ("attn", "qkv", "oproj", "gateup", "down", "lmhead")
+
+
 def measured_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary of this workload, if there is one
     (lines "traffic_bytes_per_launch <workload> <kernel> <bytes>" in profiles/*.txt)."""
@@ -43,6 +46,10 @@ def parse():
     ap.add_argument("--tau", type=float, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="also time the other thresholds of the workload's tau sweep")
+    ap.add_argument("--phases", default="gateup",
+                    help="phases bracketed by HIP events inside the timed region: one phase name (default: the dominant kernel), "
+                         "main (all six big kernels, ~6%% slower steps) or none; the per-kernel table of the other phases comes "
+                         "from up to 32 extra untimed steps")
     ap.add_argument("--profile-all", action="store_true", help="bracket every phase with events (adds overhead)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one plain 1 GiB device copy first: under rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE give the counter scale")
@@ -80,13 +87,15 @@ def algorithmic_bytes(m, esz, lens_sum, R):
     return weights, kv
 
 
-def run_tau(ctx, m, r, prompts, tau_idx, steps, warmup, prof_phases):
+def run_tau(ctx, m, r, prompts, tau_idx, steps, warmup, prof_phases, table_steps=0):
+    """Warm-up, then the timed region (only `prof_phases` carry events: every bracketed phase costs two event records
+    per launch), then `table_steps` untimed extra steps with every main phase bracketed for the per-kernel table."""
     import torch
     B, D = len(prompts), r.block_D
     ctx.prefill(prompts)
     torch.cuda.synchronize()
-    ids = torch.zeros(warmup + steps, B, D, dtype=torch.int32, device="cuda")
-    cnt = torch.zeros(warmup + steps, B, dtype=torch.int32, device="cuda")
+    ids = torch.zeros(warmup + steps + table_steps, B, D, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(warmup + steps + table_steps, B, dtype=torch.int32, device="cuda")
     for t in range(warmup):
         ctx.decode_step(ids[t], cnt[t])
         ctx.kv_commit()
@@ -99,9 +108,17 @@ def run_tau(ctx, m, r, prompts, tau_idx, steps, warmup, prof_phases):
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     phases = ctx.profile_read()
+    table = {}
+    if table_steps:
+        ctx.profile(MAIN_PHASES)
+        for t in range(warmup + steps, warmup + steps + table_steps):
+            ctx.decode_step(ids[t], cnt[t])
+            ctx.kv_commit()
+        torch.cuda.synchronize()
+        table = ctx.profile_read()
     ctx.profile(None)
     n, c = ctx.get_lengths()
-    return t1 - t0, cnt.cpu(), phases, n
+    return t1 - t0, cnt.cpu(), phases, n, table
 
 
 def cpu_baseline(m, host_g, host_layers, prompt, D, tau, budget_s=12.0, max_steps=64, prompt_tokens=8):
@@ -152,7 +169,8 @@ def main():
     taus = [tau] + ([t for t in (r.taus or []) if t != tau] if a.sweep else [])
     B, D = r.batch, r.block_D
     prompts = [p.numpy() for p in syn.make_prompts(wl.seed, B, r.prompt_lo, r.prompt_hi, m.vocab)]
-    total_steps = a.warmup + a.steps
+    table_steps = 0 if (a.profile_all or a.phases == "main") else min(32, a.steps)
+    total_steps = a.warmup + a.steps + table_steps
     max_len = max(len(p) for p in prompts) + total_steps * D + D
     n_pages = sum((len(p) + total_steps * D + D + 15) // 16 + 1 for p in prompts) if r.paged else 0
     ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=B, max_seq_len=max_len, block_D=D, tau=tau, paged=r.paged,
@@ -161,7 +179,7 @@ def main():
     t0 = time.perf_counter()
     host_g, host_layers = build_model(ctx, m, wl.seed, keep_host_layers=m.n_layers if want_cpu else None)
     t_build = time.perf_counter() - t0
-    prof = True if a.profile_all else ("attn", "qkv", "oproj", "gateup", "down", "lmhead")
+    prof = True if a.profile_all else {"main": MAIN_PHASES, "none": None}.get(a.phases, (a.phases,))
     esz = 4 if m.dtype == "fp32" else 2
     results = []
     for ti, tv in enumerate(taus):
@@ -170,19 +188,19 @@ def main():
             ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=B, max_seq_len=max_len, block_D=D, tau=tv, paged=r.paged, n_pages=n_pages)
             build_model(ctx, m, wl.seed)
         t0 = time.perf_counter()
-        dt, cnt, phases, n_end = run_tau(ctx, m, r, prompts, ti, a.steps, a.warmup, prof)
+        dt, cnt, phases, n_end, tphases = run_tau(ctx, m, r, prompts, ti, a.steps, a.warmup, prof, table_steps if ti == 0 else 0)
         t_total = time.perf_counter() - t0
-        timed = cnt[a.warmup:].numpy().astype(np.int64)
+        timed = cnt[a.warmup:a.warmup + a.steps].numpy().astype(np.int64)
         accepted = int(timed.sum())
         hist = np.bincount(timed.ravel(), minlength=D + 1)[1:].tolist()
         # context length of every sequence at every timed step (prompt + everything accepted before the step)
         lens0 = np.array([len(p) for p in prompts], dtype=np.int64)
         before = lens0[None, :] + np.concatenate([np.zeros((1, B), np.int64), np.cumsum(cnt.numpy().astype(np.int64), 0)[:-1]], 0)
-        ctx_timed = before[a.warmup:]
-        pend = np.concatenate([np.zeros((1, B), np.int64), cnt.numpy().astype(np.int64)[:-1]], 0)[a.warmup:]
+        ctx_timed = before[a.warmup:a.warmup + a.steps]
+        pend = np.concatenate([np.zeros((1, B), np.int64), cnt.numpy().astype(np.int64)[:-1]], 0)[a.warmup:a.warmup + a.steps]
         R_mean = float((pend + D).sum(1).mean())
         w_bytes, kv_bytes = algorithmic_bytes(m, esz, float(ctx_timed.sum(1).mean()), R_mean)
-        results.append(dict(tau=tv, dt=dt, accepted=accepted, hist=hist, phases=phases, R_mean=R_mean,
+        results.append(dict(tau=tv, dt=dt, accepted=accepted, hist=hist, phases=phases, tphases=tphases, R_mean=R_mean,
                             w_bytes=w_bytes, kv_bytes=kv_bytes, ctx_mean=float(ctx_timed.mean()), t_total=t_total))
     main_r = results[0]
     ms_per_step = 1e3 * main_r["dt"] / a.steps
@@ -204,16 +222,21 @@ def main():
     table = {}
     for name, k in kern.items():
         ms, launches = main_r["phases"].get(name, (0.0, 0))
+        src = "timed region"
+        if launches == 0:
+            ms, launches = main_r["tphases"].get(name, (0.0, 0))
+            src = "extra steps after the timed region"
         if launches == 0:
             continue
         avg = ms / launches
         t_hbm = k["bytes"] / (PEAK_HBM_GBS * 1e9)
         t_mfma = k["flops"] / (PEAK_BF16_TFLOPS * 1e12)
         table[name] = dict(ms_total=ms, launches=launches, avg_us=1e3 * avg, gbs=k["bytes"] / (avg * 1e-3) / 1e9,
-                           tflops=k["flops"] / (avg * 1e-3) / 1e12, bound="hbm" if t_hbm >= t_mfma or m.dtype == "fp32" else "mfma")
+                           tflops=k["flops"] / (avg * 1e-3) / 1e12, bound="hbm" if t_hbm >= t_mfma or m.dtype == "fp32" else "mfma",
+                           per_step_ms=ms / launches * (1 if name == "lmhead" else L), events=src)
     roof = None
     if table:
-        dom = max(table, key=lambda k: table[k]["ms_total"])
+        dom = max(table, key=lambda k: table[k]["per_step_ms"])
         t = table[dom]
         if t["bound"] == "hbm":
             roof = dict(kernel=dom, bound="hbm", achieved=t["gbs"], peak=PEAK_HBM_GBS, unit="GB/s", frac=t["gbs"] / PEAK_HBM_GBS, traffic=None)
@@ -223,6 +246,7 @@ def main():
         roof["traffic"] = measured_traffic(a.config, dom)
         roof["avg_launch_us"] = t["avg_us"]
         roof["launches"] = t["launches"]
+        roof["events"] = t["events"]
     step_bytes = main_r["w_bytes"] + main_r["kv_bytes"]
     out = {
         "metric": "accepted tokens/sec and block-step latency; achieved HBM GB/s vs peak",

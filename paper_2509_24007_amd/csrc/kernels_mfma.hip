@@ -73,8 +73,12 @@ enum { EPI_LMHEAD = 4 };
 
 __device__ inline float silu_f(float v) { return v / (1.0f + __expf(-v)); }
 
+// The largest tile keeps two register sets of weights instead of three so that accumulators + operands fit in 256
+// registers: two workgroups then share a compute unit and one's barrier and load waits are covered by the other.
+template <int MT, int NT> constexpr int w_sets() { return (MT == 4) ? 2 : 3; }
+
 template <int MT, int NT, int EPI>
-__global__ __launch_bounds__(256) void gemm_mfma_k(MfmaArgs a)
+__global__ __launch_bounds__(256, (w_sets<MT, NT>() == 2 ? 2 : 1)) void gemm_mfma_k(MfmaArgs a)
 {
     __shared__ __attribute__((aligned(16))) bf16_t Xs[2][MT * 32][XS_STRIDE];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -121,7 +125,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_k(MfmaArgs a)
     // static names); the activations go registers -> LDS at the bottom of the slice.  Activation loads are issued
     // before the weight loads: the counter that orders returns is in program order, so waiting for the (L2-hot)
     // activations leaves the (HBM) weight loads in flight.
-    bf16x8 w0[NT][4], w1[NT][4], w2[NT][4];
+    bf16x8 w0[NT][4], w1[NT][4], w2[w_sets<MT, NT>() == 3 ? NT : 1][4];
     u32x4 xr[MT];
     const int s_last = s_end - 1;
 #define SDLM_LOAD_W(dst, stage)                                                                                   \
@@ -136,8 +140,9 @@ __global__ __launch_bounds__(256) void gemm_mfma_k(MfmaArgs a)
         _Pragma("unroll") for (int i = 0; i < MT; ++i) xr[i] = *(const u32x4 *)(a.X + xo_ + xoff[i]);                    \
     }
     SDLM_LOAD_X(s_begin);
+    constexpr int WSETS = w_sets<MT, NT>();
     SDLM_LOAD_W(w0, s_begin);
-    SDLM_LOAD_W(w1, s_begin + 1);
+    if (WSETS == 3) SDLM_LOAD_W(w1, s_begin + 1);
 #pragma unroll
     for (int i = 0; i < MT; ++i) *(u32x4 *)&Xs[0][i * 32 + xrow][xchunk * 8] = xr[i];
     __syncthreads();
@@ -147,23 +152,34 @@ __global__ __launch_bounds__(256) void gemm_mfma_k(MfmaArgs a)
 /* one k-step: request the LDS operands of the next k-step, run this k-step's MFMAs, and pin that order */
 #define SDLM_KSTEP(WC, ks, has_next)                                                                              \
     {                                                                                                             \
-        if (has_next) {                                                                                           \
+        if (WSETS == 3) {                                                                                         \
+            if (has_next) {                                                                                       \
+                _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                                \
+                    bn_[mt] = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][((ks) + 1) * 16 + bk];                    \
+            }                                                                                                     \
             _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                                    \
-                bn_[mt] = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][((ks) + 1) * 16 + bk];                        \
+                _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                \
+                    acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WC[nt][ks], bc_[mt], acc[nt][mt], 0, 0, 0); \
+            __builtin_amdgcn_sched_group_barrier(0x100, (has_next) ? MT : 0, 0);                                  \
+            __builtin_amdgcn_sched_group_barrier(0x008, MT * NT, 0);                                              \
+            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) bc_[mt] = bn_[mt];                                 \
+        } else {                                                                                                  \
+            /* one operand set: each fragment is re-read in place right after the MFMAs that used it */           \
+            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                                  \
+                _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                \
+                    acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WC[nt][ks], bc_[mt], acc[nt][mt], 0, 0, 0); \
+                if (has_next) bc_[mt] = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][((ks) + 1) * 16 + bk];          \
+                __builtin_amdgcn_sched_group_barrier(0x008, NT, 0);                                               \
+                __builtin_amdgcn_sched_group_barrier(0x100, (has_next) ? 1 : 0, 0);                               \
+            }                                                                                                     \
         }                                                                                                         \
-        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                                        \
-            _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                    \
-                acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WC[nt][ks], bc_[mt], acc[nt][mt], 0, 0, 0); \
-        __builtin_amdgcn_sched_group_barrier(0x100, (has_next) ? MT : 0, 0);                                      \
-        __builtin_amdgcn_sched_group_barrier(0x008, MT * NT, 0);                                                  \
-        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) bc_[mt] = bn_[mt];                                     \
     }
 #define SDLM_STAGE(WC, WN, stage)                                                                                 \
     {                                                                                                             \
         SDLM_LOAD_X((stage) + 1);                                                                                 \
-        SDLM_LOAD_W(WN, (stage) + 2);                                                                             \
+        SDLM_LOAD_W(WN, (stage) + WSETS - 1);                                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                                        \
-        bf16x8 bc_[MT], bn_[MT];                                                                                  \
+        bf16x8 bc_[MT], bn_[WSETS == 3 ? MT : 1];                                                                                  \
         _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) bc_[mt] = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][bk]; \
         __builtin_amdgcn_sched_group_barrier(0x100, MT, 0);                                                       \
         SDLM_KSTEP(WC, 0, 1) SDLM_KSTEP(WC, 1, 1) SDLM_KSTEP(WC, 2, 1) SDLM_KSTEP(WC, 3, 0)                       \
@@ -175,14 +191,22 @@ __global__ __launch_bounds__(256) void gemm_mfma_k(MfmaArgs a)
     // Full triples run without any branch inside the loop (a conditional stage would make the compiler drain all
     // outstanding loads at the loop head); the 0..2 remaining slices are peeled.
     int s = s_begin;
-    for (; s + 3 <= s_end; s += 3) {
-        SDLM_STAGE(w0, w2, s)
-        SDLM_STAGE(w1, w0, s + 1)
-        SDLM_STAGE(w2, w1, s + 2)
-    }
-    if (s < s_end) {
-        SDLM_STAGE(w0, w2, s)
-        if (s + 1 < s_end) SDLM_STAGE(w1, w0, s + 1)
+    if (WSETS == 3) {
+        for (; s + 3 <= s_end; s += 3) {
+            SDLM_STAGE(w0, w2, s)
+            SDLM_STAGE(w1, w0, s + 1)
+            SDLM_STAGE(w2, w1, s + 2)
+        }
+        if (s < s_end) {
+            SDLM_STAGE(w0, w2, s)
+            if (s + 1 < s_end) SDLM_STAGE(w1, w0, s + 1)
+        }
+    } else {
+        for (; s + 2 <= s_end; s += 2) {
+            SDLM_STAGE(w0, w1, s)
+            SDLM_STAGE(w1, w0, s + 1)
+        }
+        if (s < s_end) SDLM_STAGE(w0, w1, s)
     }
 #undef SDLM_STAGE
 #undef SDLM_KSTEP
