@@ -84,6 +84,10 @@ def lib():
         L.orc_seq_step.argtypes = [vp, i32, f32, i32, i32, vp, vp, vp, vp]
         L.orc_seq_commit.restype = C.c_int
         L.orc_seq_commit.argtypes = [vp, vp, i32]
+        L.orc_gamma_verify.restype = i32
+        L.orc_gamma_verify.argtypes = [vp, vp, i32, i32]
+        L.orc_seq_verify.restype = C.c_int
+        L.orc_seq_verify.argtypes = [vp, i32, vp, vp, vp]
         L.orc_seq_read_kv.restype = C.c_int
         L.orc_seq_read_kv.argtypes = [vp, i32, i32, i32, vp, vp]
         L.orc_probe_logit.restype = f64
@@ -215,6 +219,12 @@ def gamma(conf, tau: float, rule: int = 0) -> int:
     return int(lib().orc_gamma(_ptr(c), c.size, float(tau), rule))
 
 
+def gamma_verify(yhat, ytilde, rule: int = 0) -> int:
+    a, b = _i32(yhat), _i32(ytilde)
+    assert a.size == b.size
+    return int(lib().orc_gamma_verify(_ptr(a), _ptr(b), a.size, rule))
+
+
 def block_mask(n: int, D: int) -> np.ndarray:
     T = n + D - 1
     m = np.zeros((T, T), dtype=np.uint8)
@@ -281,6 +291,7 @@ class Seq:
         rc = lib().orc_seq_step(self.h, D, float(tau), rule, conf_fn, _ptr(logits), _ptr(ids), _ptr(conf),
                                 C.addressof(g))
         assert rc == 0, rc
+        self._last_D = D
         return logits, ids, conf, int(g.value)
 
     def commit(self, ids=None, count: int = 0) -> int:
@@ -288,6 +299,16 @@ class Seq:
             return int(lib().orc_seq_commit(self.h, None, 0))
         ids = _i32(ids)
         return int(lib().orc_seq_commit(self.h, _ptr(ids), int(count)))
+
+    def verify(self, rule: int = 0, want_logits: bool = False):
+        """Second pass of a self-speculative step -> (ytilde[D], gamma_verify[, logits[D,V] (row 0 unused)])."""
+        D = self._last_D
+        logits = np.zeros((D, self.model.vocab), dtype=np.float64) if want_logits else None
+        yt = np.empty(D, dtype=np.int32)
+        g = C.c_int32(0)
+        rc = lib().orc_seq_verify(self.h, rule, _ptr(logits), _ptr(yt), C.addressof(g))
+        assert rc == 0, rc
+        return (yt, int(g.value), logits) if want_logits else (yt, int(g.value))
 
     @property
     def n(self) -> int:

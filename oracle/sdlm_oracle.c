@@ -599,6 +599,84 @@ int orc_seq_commit(orc_seq *s, const int32_t *ids, int32_t count)
     return 0;
 }
 
+/* ------------------------------- self-speculative verification (Sec. 3.4, Eq. 10) */
+
+/*
+ * gamma_verify from the speculative tokens yhat[0..D) and the verification
+ * predictions ytilde[0..D).  rule 1 is the equation as printed: the largest j
+ * with yhat^j == ytilde^j, or 1.  rule 0 is the reading used by default: the
+ * longest prefix on which every position agrees (ytilde^j is computed with
+ * yhat^1..yhat^{j-1} as context, so it says nothing once one of them is wrong),
+ * or 1.
+ */
+int32_t orc_gamma_verify(const int32_t *yhat, const int32_t *ytilde, int32_t D, int32_t rule)
+{
+    int32_t best = 1;
+    if (rule == 1) {
+        for (int32_t j = 1; j <= D; ++j)
+            if (yhat[j - 1] == ytilde[j - 1] && j > best) best = j;
+    } else {
+        int32_t j = 0;
+        while (j < D && yhat[j] == ytilde[j]) ++j;
+        if (j > best) best = j;
+    }
+    return best;
+}
+
+/* A deep copy of the sequence with room for max_len positions. */
+static orc_seq *seq_clone(const orc_seq *s, int32_t max_len)
+{
+    orc_seq *t = orc_seq_new(&s->cfg, s->w, max_len);
+    size_t kd = (size_t)s->cfg.n_kv_heads * s->cfg.head_dim;
+    t->n = s->n; t->c = s->c;
+    memcpy(t->tokens, s->tokens, sizeof(int32_t) * (size_t)s->n);
+    for (int l = 0; l < s->cfg.n_layers; ++l) {
+        memcpy(t->K + (size_t)l * max_len * kd, s->K + (size_t)l * s->max_len * kd, sizeof(double) * (size_t)s->n * kd);
+        memcpy(t->V + (size_t)l * max_len * kd, s->V + (size_t)l * s->max_len * kd, sizeof(double) * (size_t)s->n * kd);
+    }
+    return t;
+}
+
+/*
+ * Second pass of a self-speculative step, after orc_seq_step produced the D
+ * speculative tokens yhat.  Verification input j (j = 1..D) is the sequence
+ * extended by yhat^1..yhat^{j-1} with the mask tokens following it, i.e. exactly
+ * the input of an ordinary block-decode step on that longer sequence; ytilde^j is
+ * the token that step predicts first.  Input 1 is the first pass itself, so
+ * ytilde^1 = yhat^1.  Each input is run on its own copy of the sequence.
+ * logits_out (optional) [D][V]: row j-1 = the logits ytilde^j was taken from (row 0
+ * is not written).  On success the step's gamma becomes gamma_verify, which is
+ * what a commit without arguments then publishes.
+ */
+int orc_seq_verify(orc_seq *s, int32_t rule, double *logits_out, int32_t *ytilde, int32_t *gamma)
+{
+    if (!s->step_valid) return -3;
+    const int D = s->last_D, V = s->cfg.vocab;
+    ytilde[0] = s->last_ids[0];
+    double *z = malloc(sizeof(double) * (size_t)D * V);
+    int32_t *ids = malloc(sizeof(int32_t) * (size_t)D);
+    float *conf = malloc(sizeof(float) * (size_t)D);
+    int rc = 0;
+    for (int j = 2; j <= D && rc == 0; ++j) {
+        orc_seq *t = seq_clone(s, s->n + 2 * D);
+        t->step_valid = 1; t->last_D = D;
+        rc = orc_seq_commit(t, s->last_ids, j - 1);
+        int32_t g;
+        if (rc == 0) rc = orc_seq_step(t, D, 1.0f, 0, 0, z, ids, conf, &g);
+        if (rc == 0) {
+            ytilde[j - 1] = ids[0];
+            if (logits_out) memcpy(logits_out + (size_t)(j - 1) * V, z, sizeof(double) * (size_t)V);
+        }
+        orc_seq_free(t);
+    }
+    if (rc == 0) {
+        *gamma = orc_gamma_verify(s->last_ids, ytilde, D, rule);
+        s->last_gamma = *gamma;
+    }
+    free(z); free(ids); free(conf);
+    return rc;
+}
+
 /* Read back a cached K or V vector (layer, position, kv head) for tests. */
 int orc_seq_read_kv(const orc_seq *s, int32_t layer, int32_t pos, int32_t kv_head, double *k_out, double *v_out)
 {
