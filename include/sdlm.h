@@ -137,6 +137,24 @@ int sdlm_prefill(sdlm_ctx *ctx, int32_t batch, const int32_t *ids_packed, const 
 int sdlm_decode_step(sdlm_ctx *ctx, int32_t *ids, int32_t *count, float *conf, float *logits);
 
 /*
+ * Second pass of a self-speculative step (Sec. 3.4, "Self-Speculative Decoding", Eq. 10); call it between
+ * sdlm_decode_step, whose D arg-max tokens are the speculative tokens yhat^1..yhat^D, and sdlm_kv_commit.
+ * Verification input j (j = 2..D) is the sequence extended by yhat^1..yhat^{j-1} followed by the mask tokens, i.e.
+ * the input of an ordinary block step on that longer sequence; ytilde^j is the token that step would predict first
+ * (input 1 is the first pass itself, so ytilde^1 = yhat^1).  All D-1 inputs of all sequences run as one batch of
+ * rows through the same kernels as the step; they read the cache and write nothing to it.
+ *   rule       0: gamma_verify = length of the longest prefix on which yhat and ytilde agree (at least 1);
+ *              1: the equation as printed: the largest j with yhat^j == ytilde^j (at least 1).
+ *   ids_tilde  [dev, batch x D] ytilde, or NULL.
+ *   count      [dev, batch] gamma_verify, or NULL.  It also replaces the step's own count, so that a commit
+ *              without overrides publishes yhat^1..yhat^{gamma_verify}.
+ *   logits     [dev, batch x (D-1) x vocab] fp32 logits from which ytilde^2..ytilde^D were taken, or NULL.
+ * Asynchronous on the context's stream.  Errors: SDLM_ESTATE without a preceding step, SDLM_EINVAL for an unknown
+ * rule or when 2D-2 exceeds the 16 slots of a staging tile (block_D > 9).
+ */
+int sdlm_verify_step(sdlm_ctx *ctx, int32_t rule, int32_t *ids_tilde, int32_t *count, float *logits);
+
+/*
  * Publish the last step: the pending tokens' K/V become part of the cache (c_b = n_b) and the accepted tokens
  * become the next step's pending tokens (n_b += count_b); in the paged layout the page table grows to back
  * every position < n_b.  With both arguments NULL the step's own result is committed.  With ids_override

@@ -9,8 +9,9 @@
 // workgroup copies a tile pair (32 keys, 16 KB) global -> LDS as one contiguous run and every wavefront reads its
 // operands from LDS with conflict-free 16-byte / 8-byte reads.  Each of the four wavefronts owns 16 of the (at
 // most 64) query vectors, so its state is small (32 accumulator registers) and four workgroups fit on a CU.
-// The mask of the method lives in registers: a pending row at position p sees cache keys [0, p]; a block row
-// sees cache keys [0, s) and the D keys of its own block (held in the sequence's staging tile).
+// The mask of the method lives in registers: every row sees cache keys [0, lim) and the first slim slots of the
+// group's staging tile.  A pending row at position p has lim = p + 1 and no staging slots; a block row has lim = s
+// and the D keys of its own block in the staging tile.
 // Chunks of one (group, head) are merged by a second small kernel when there is more than one.
 #include "mfma.hpp"
 
@@ -50,7 +51,7 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
     const int G = a.G, QR = nrows * G;
 
     int lim_l = lane < nrows ? a.rm.lim[row0 + lane] : 0;
-    int blk_l = lane < nrows ? (a.rm.kind[row0 + lane] >= 0 ? 1 : 0) : 0;
+    int blk_l = lane < nrows ? (a.rm.slim[row0 + lane] > 0 ? 1 : 0) : 0;
     int min_l = lane < nrows ? lim_l : 0x7fffffff;
     for (int o = 32; o > 0; o >>= 1) {
         lim_l = max(lim_l, __shfl_xor(lim_l, o));
@@ -72,7 +73,7 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
     const bool wave_active = wave * 16 < QR;
     const int rl = qvalid ? qi / G : 0, hg = qvalid ? qi % G : 0, qrow = row0 + rl;
     const int lim_q = qvalid ? a.rm.lim[qrow] : 0;
-    const bool blk_q = qvalid && a.rm.kind[qrow] >= 0;
+    const int slim_q = qvalid ? a.rm.slim[qrow] : 0;   // staging slots this query sees
     Op8 qop[4];
     {
         const bf16_t *qp = a.q + ((size_t)qrow * a.Hq + hk * G + hg) * HD + lg * 8;
@@ -92,7 +93,7 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
     __shared__ __attribute__((aligned(16))) bf16_t kv[2][2][2 * PAGE * HD];   // [buffer][tile A/B][K block | V block]
     const int32_t *ptab = a.st.page_table + (size_t)b * a.kg.pages_per_seq;
     const size_t tile_elems = 2 * PAGE * HD;
-    const int stg_page = a.kg.staging_base + b;
+    const int stg_page = max(a.rm.grp_stg[g], 0);
     u32x4 r[4];
     auto fetch = [&](int pp) {
         const int uA = 2 * pp, uB = 2 * pp + 1;
@@ -138,8 +139,8 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
                 const int keyA = (c0 + uA) * PAGE + lg * 4, keyB = (c0 + uB) * PAGE + lg * 4;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    bool visA = stgA ? (blk_q && lg * 4 + v < a.D) : (keyA + v < lim_q);
-                    bool visB = hasB && (stgB ? (blk_q && lg * 4 + v < a.D) : (keyB + v < lim_q));
+                    bool visA = stgA ? (lg * 4 + v < slim_q) : (keyA + v < lim_q);
+                    bool visB = hasB && (stgB ? (lg * 4 + v < slim_q) : (keyB + v < lim_q));
                     sA[v] = visA ? sA[v] : -INFINITY;
                     sB[v] = visB ? sB[v] : -INFINITY;
                 }
@@ -272,8 +273,11 @@ size_t mfma_attn_scratch_bytes(const sdlm_model_cfg *m, const sdlm_run_cfg *r, i
     // decode: every sequence has at most ceil(2D / gr) groups; prefill: at most max_rows groups of >= 1 row, but
     // then each group is short: bound both by the launch that needs the most (groups x chunks)
     size_t worst = 0;
-    int cand[2] = {r->max_batch * ((2 * r->block_D + gr - 1) / gr), max_rows / gr + r->max_batch};
-    for (int i = 0; i < 2; ++i) {
+    // ... and the verification pass: D-1 inputs per sequence of at most 2D-2 rows each
+    int cand[3] = {r->max_batch * ((2 * r->block_D + gr - 1) / gr), max_rows / gr + r->max_batch,
+                   r->max_batch * (r->block_D - 1) * ((2 * r->block_D - 2 + gr - 1) / gr)};
+    for (int i = 0; i < 3; ++i) {
+        if (cand[i] < 1) continue;
         int cp, mc;
         chunking(m, r->max_seq_len, cand[i], &cp, &mc);
         size_t items = (size_t)cand[i] * m->n_kv_heads * mc;

@@ -59,10 +59,13 @@ __host__ __device__ inline int v_off(int slot, int i) { return (((i >> 4) << 2) 
 
 // Packed description of the rows of one forward pass (device arrays).
 struct RowMeta {
-    int32_t *tok, *pos, *seq, *kind, *lim;  // [max_rows]; kind: -1 pending, else block index; lim: visible cache keys
-    int32_t *grp_row0, *grp_n, *grp_seq;    // [max_groups]: runs of <= GROUP_ROWS rows of one sequence
-    int32_t *blk_row;                       // [max_batch*D]: packed row index of block row (b, j)
-    int32_t *counts;                        // [4]: rows R, groups, block rows, unused
+    int32_t *tok, *pos, *seq, *kind, *lim;  // [max_rows]; kind: -1 = K/V go to the cache slot of pos, else the slot in the
+                                            // row's staging tile; lim: visible cache keys [0, lim)
+    int32_t *stg, *slim;                    // [max_rows]; staging tile of the row (-1: none) and how many of its slots the row sees
+    int32_t *grp_row0, *grp_n, *grp_seq;    // [max_groups]: runs of <= GROUP_ROWS rows of one sequence that share a staging tile
+    int32_t *grp_stg;                       // [max_groups]: that staging tile (-1: none)
+    int32_t *blk_row;                       // [max_batch*D]: packed row index of the rows that go through the LM head
+    int32_t *counts;                        // [4]: rows R, groups, LM-head rows, unused
 };
 
 // Per-sequence state (device arrays).
@@ -76,7 +79,8 @@ struct SeqState {
 };
 
 struct KvGeom {
-    int32_t n_kv_heads, head_dim, pages_per_seq, staging_base;  // staging tile of sequence b = staging_base + b
+    int32_t n_kv_heads, head_dim, pages_per_seq, staging_base;  // staging tile of sequence b = staging_base + b; the tiles of
+                                                                 // verification input (b, j) follow at staging_base + B + b (D-1) + j
     size_t layer_stride;                                         // elements per layer of the pool
     __host__ __device__ size_t tile(int page, int kvh) const { return ((size_t)page * n_kv_heads + kvh) * (size_t)(2 * PAGE * head_dim); }
 };
@@ -96,7 +100,12 @@ struct GemmArgs {
     float scale;
 };
 
-void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows);
+void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows,
+                            int staging_base);
+void launch_assemble_verify(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows,
+                            int staging_base);
+void launch_verify_accept(hipStream_t s, const SeqState &st, const int32_t *ids_rows, int B, int D, int rule,
+                          int32_t *ids_out, int32_t *count_out);
 void launch_embed(hipStream_t s, int dtype, float *x, const void *E, const RowMeta &rm, int max_rows, int h, int V);
 void launch_rmsnorm(hipStream_t s, int dtype, void *out, float *x, const void *g, int h, float eps, const int32_t *row_index,
                     const int32_t *p_count, int max_rows, const float *slabs, int n_slabs, size_t slab_stride);
@@ -104,7 +113,7 @@ void launch_gemm_generic(hipStream_t s, int dtype, int epi, const GemmArgs &a);
 void launch_rope_scatter(hipStream_t s, int dtype, const float *qkv, int n_slabs, size_t slab_stride, void *q_out, void *pool_layer,
                          const KvGeom &kg, const RowMeta &rm, const SeqState &st, const float2 *rope, int n_q_heads, int max_rows);
 void launch_attn_generic(hipStream_t s, int dtype, const void *q, void *out, const void *pool_layer, const KvGeom &kg,
-                         const RowMeta &rm, const SeqState &st, int n_q_heads, int D, int max_rows);
+                         const RowMeta &rm, const SeqState &st, int n_q_heads, int max_rows);
 void launch_lm_reduce(hipStream_t s, const float *logits, int V, int32_t *ids, float *conf, int conf_fn,
                       const int32_t *p_rows, int max_rows);
 void launch_accept(hipStream_t s, const SeqState &st, const int32_t *ids_rows, const float *conf_rows, int B, int D,

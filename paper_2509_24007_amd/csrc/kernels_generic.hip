@@ -10,7 +10,7 @@ namespace sdlm {
 // Rows of a decode step, per sequence: the pending tokens (positions c..n-1, causal), then the block
 // [x_last, [m] x (D-1)] at positions n-1 .. n+D-2 (block definition, Sec. 3.2).  A block row may see the cache
 // below position s = n-1 only; the causal copy of x_last at s is for later steps.
-__global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mask_id, int gr)
+__global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mask_id, int gr, int stg0)
 {
     __shared__ int row0[1025], grp0[1025];
     if (threadIdx.x == 0) {
@@ -30,10 +30,12 @@ __global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mas
         for (int i = 0; i < p; ++i, ++r) {
             rm.tok[r] = st.pend_tok[b * D + i];
             rm.pos[r] = c + i; rm.seq[r] = b; rm.kind[r] = -1; rm.lim[r] = c + i + 1;
+            rm.stg[r] = -1; rm.slim[r] = 0;
         }
         for (int j = 0; j < D; ++j, ++r) {
             rm.tok[r] = j == 0 ? st.last_tok[b] : mask_id;
             rm.pos[r] = n - 1 + j; rm.seq[r] = b; rm.kind[r] = j; rm.lim[r] = n - 1;
+            rm.stg[r] = stg0 + b; rm.slim[r] = D;
             rm.blk_row[b * D + j] = r;
         }
         int rows = p + D, g = grp0[b];
@@ -41,13 +43,95 @@ __global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mas
             rm.grp_row0[g] = row0[b] + o;
             rm.grp_n[g] = min(gr, rows - o);
             rm.grp_seq[g] = b;
+            rm.grp_stg[g] = stg0 + b;
         }
     }
 }
 
-void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows)
+void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows, int staging_base)
 {
-    hipLaunchKernelGGL(assemble_decode_k, dim3(1), dim3(256), 0, s, st, rm, B, D, mask_id, group_rows);
+    hipLaunchKernelGGL(assemble_decode_k, dim3(1), dim3(256), 0, s, st, rm, B, D, mask_id, group_rows, staging_base);
+}
+
+// Rows of the verification pass of a self-speculative step (Sec. 3.4, "Self-Speculative Decoding").  With yhat^1..yhat^D
+// the tokens of the step just computed and n the number of known tokens, verification input j (j = 2..D; input 1 is
+// the step itself) is the sequence extended by yhat^1..yhat^{j-1}.  It is laid out as a self-contained run of rows:
+//   j-2 causal rows   yhat^1..yhat^{j-2} at positions n..n+j-3
+//   D block rows      [yhat^{j-1}, [m] x (D-1)] at positions n+j-2 ..
+// All of them see the cache keys [0, n) (written by the step: every known token including x_last has its causal K/V
+// there) and keep their own K/V in the input's staging tile: a causal row in slot i sees slots [0, i]; a block row
+// sees all j-2+D slots.  Nothing is written to the cache.  Only the first block row of each input goes through the
+// LM head: its arg-max is ytilde^j.
+__global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mask_id, int gr, int stg0)
+{
+    __shared__ int row0[1025], grp0[1025];
+    const int rows_seq = (D - 1) * D + (D - 2) * (D - 1) / 2;
+    if (threadIdx.x == 0) {
+        int g = 0;
+        for (int b = 0; b < B; ++b) {
+            row0[b] = b * rows_seq; grp0[b] = g;
+            for (int j = 2; j <= D; ++j) g += (j - 2 + D + gr - 1) / gr;
+        }
+        rm.counts[0] = B * rows_seq; rm.counts[1] = g; rm.counts[2] = B * (D - 1); rm.counts[3] = 0;
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+        const int n = st.n[b];
+        const int32_t *yhat = st.last_ids + b * D;
+        int r = row0[b], g = grp0[b];
+        for (int j = 2; j <= D; ++j) {
+            const int tile = stg0 + B + b * (D - 1) + (j - 2), ns = j - 2 + D, first = r;
+            for (int i = 0; i < j - 2; ++i, ++r) {
+                rm.tok[r] = yhat[i]; rm.pos[r] = n + i; rm.seq[r] = b; rm.kind[r] = i; rm.lim[r] = n;
+                rm.stg[r] = tile; rm.slim[r] = i + 1;
+            }
+            for (int t = 0; t < D; ++t, ++r) {
+                rm.tok[r] = t == 0 ? yhat[j - 2] : mask_id; rm.pos[r] = n + j - 2 + t; rm.seq[r] = b; rm.kind[r] = j - 2 + t;
+                rm.lim[r] = n; rm.stg[r] = tile; rm.slim[r] = ns;
+                if (t == 0) rm.blk_row[b * (D - 1) + (j - 2)] = r;
+            }
+            for (int o = 0; o < ns; o += gr, ++g) {
+                rm.grp_row0[g] = first + o;
+                rm.grp_n[g] = min(gr, ns - o);
+                rm.grp_seq[g] = b;
+                rm.grp_stg[g] = tile;
+            }
+        }
+    }
+}
+
+void launch_assemble_verify(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows,
+                            int staging_base)
+{
+    hipLaunchKernelGGL(assemble_verify_k, dim3(1), dim3(256), 0, s, st, rm, B, D, mask_id, group_rows, staging_base);
+}
+
+// gamma_verify (Eq. 10) from the step's tokens yhat and the verification predictions (ids_rows: ytilde^2..ytilde^D per
+// sequence; ytilde^1 = yhat^1 because input 1 is the step itself).  rule 0: longest prefix on which all positions
+// agree; rule 1: the largest agreeing index, as the equation is printed.  The result replaces the step's own count,
+// so that a commit without overrides publishes the verified tokens.
+__global__ void verify_accept_k(SeqState st, const int32_t *ids_rows, int B, int D, int rule, int32_t *ids_out, int32_t *count_out)
+{
+    int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const int32_t *yhat = st.last_ids + b * D;
+    int best = 1;
+    bool run = true;
+    for (int j = 1; j <= D; ++j) {
+        int yt = j == 1 ? yhat[0] : ids_rows[b * (D - 1) + (j - 2)];
+        if (ids_out) ids_out[b * D + j - 1] = yt;
+        bool eq = yt == yhat[j - 1];
+        run = run && eq;
+        if (rule == 1 ? eq : run) best = j;
+    }
+    st.last_count[b] = best;
+    if (count_out) count_out[b] = best;
+}
+
+void launch_verify_accept(hipStream_t s, const SeqState &st, const int32_t *ids_rows, int B, int D, int rule,
+                          int32_t *ids_out, int32_t *count_out)
+{
+    hipLaunchKernelGGL(verify_accept_k, dim3((B + 63) / 64), dim3(64), 0, s, st, ids_rows, B, D, rule, ids_out, count_out);
 }
 
 // ------------------------------------------------------------------------------------------------ embedding
@@ -197,7 +281,7 @@ void launch_gemm_generic(hipStream_t s, int dtype, int epi, const GemmArgs &a)
 // ------------------------------------------------------------------------------------------------ RoPE + K/V placement
 // qkv: raw projections [R, (Hq + 2 Hkv) d] fp32, given as n_slabs partial sums that are added in order.  Queries and keys are rotated at the row's position (rotate-half
 // pairing i <-> i + d/2).  A pending row's K/V go to the cache slot of its position: they are final.  A block
-// row's K/V go to its sequence's staging tile, slot = block index: they are never cached.
+// row's K/V (and, in a verification pass, every row's) go to slot `kind` of the row's staging tile: they are never cached.
 template <typename T>
 __global__ __launch_bounds__(256) void rope_scatter_k(const float *qkv, int n_slabs, size_t slab_stride, T *q_out, T *pool, KvGeom kg,
                                                       RowMeta rm, SeqState st, const float2 *rope, int Hq)
@@ -215,7 +299,7 @@ __global__ __launch_bounds__(256) void rope_scatter_k(const float *qkv, int n_sl
     const float2 *cs = rope + (size_t)pos * half;
     int page, slot;
     if (kind < 0) { page = st.page_table[(size_t)b * kg.pages_per_seq + pos / PAGE]; slot = pos % PAGE; }
-    else { page = kg.staging_base + b; slot = kind; }
+    else { page = rm.stg[r]; slot = kind; }
     for (int e = threadIdx.x; e < Hq * half; e += 256) {
         int hq = e / half, i = e % half;
         float2 t = cs[i];
@@ -246,19 +330,19 @@ void launch_rope_scatter(hipStream_t s, int dtype, const float *qkv, int n_slabs
 }
 
 // ------------------------------------------------------------------------------------------------ attention
-// One wavefront per (row, query head).  Keys: the cache positions [0, lim) of the row's sequence and, for a
-// block row, the D staging keys of the block (mask equation, Sec. 3.3: causal below the block start, full
-// mutual attention inside the block).  Each lane walks a strided subset of the keys with a running
+// One wavefront per (row, query head).  Keys: the cache positions [0, lim) of the row's sequence and the first
+// slim slots of the row's staging tile; for a block row these are the D keys of its block (mask equation, Sec. 3.3:
+// causal below the block start, full mutual attention inside the block).  Each lane walks a strided subset of the keys with a running
 // (max, sum, output); the 64 partial results are merged at the end.
 template <typename T, int HD>
 __global__ __launch_bounds__(64) void attn_generic_k(const T *q, T *out, const T *pool, KvGeom kg, RowMeta rm, SeqState st,
-                                                     int Hq, int D)
+                                                     int Hq)
 {
     const int r = blockIdx.y;
     if (r >= rm.counts[0]) return;
     const int hq = blockIdx.x, G = Hq / kg.n_kv_heads, hk = hq / G, lane = threadIdx.x;
-    const int b = rm.seq[r], lim = rm.lim[r], kind = rm.kind[r];
-    const int total = lim + (kind >= 0 ? D : 0);
+    const int b = rm.seq[r], lim = rm.lim[r], stg = rm.stg[r];
+    const int total = lim + (stg >= 0 ? rm.slim[r] : 0);
     __shared__ float qs[HD];
     __shared__ float part[64][HD + 1];
     const float scale = 1.0f / sqrtf((float)HD);
@@ -270,7 +354,7 @@ __global__ __launch_bounds__(64) void attn_generic_k(const T *q, T *out, const T
     for (int j = lane; j < total; j += 64) {
         int page, slot;
         if (j < lim) { page = st.page_table[(size_t)b * kg.pages_per_seq + j / PAGE]; slot = j % PAGE; }
-        else { page = kg.staging_base + b; slot = j - lim; }
+        else { page = stg; slot = j - lim; }
         const T *Kb = pool + kg.tile(page, hk), *Vb = Kb + PAGE * HD;
         float sdot = 0.f;
 #pragma unroll
@@ -299,22 +383,22 @@ __global__ __launch_bounds__(64) void attn_generic_k(const T *q, T *out, const T
 
 template <typename T>
 static void attn_generic_t(hipStream_t s, const void *q, void *out, const void *pool_layer, const KvGeom &kg,
-                           const RowMeta &rm, const SeqState &st, int Hq, int D, int max_rows)
+                           const RowMeta &rm, const SeqState &st, int Hq, int max_rows)
 {
     dim3 grid(Hq, max_rows), block(64);
     switch (kg.head_dim) {
-    case 32: hipLaunchKernelGGL((attn_generic_k<T, 32>), grid, block, 0, s, (const T *)q, (T *)out, (const T *)pool_layer, kg, rm, st, Hq, D); break;
-    case 64: hipLaunchKernelGGL((attn_generic_k<T, 64>), grid, block, 0, s, (const T *)q, (T *)out, (const T *)pool_layer, kg, rm, st, Hq, D); break;
-    case 96: hipLaunchKernelGGL((attn_generic_k<T, 96>), grid, block, 0, s, (const T *)q, (T *)out, (const T *)pool_layer, kg, rm, st, Hq, D); break;
-    default: hipLaunchKernelGGL((attn_generic_k<T, 128>), grid, block, 0, s, (const T *)q, (T *)out, (const T *)pool_layer, kg, rm, st, Hq, D); break;
+    case 32: hipLaunchKernelGGL((attn_generic_k<T, 32>), grid, block, 0, s, (const T *)q, (T *)out, (const T *)pool_layer, kg, rm, st, Hq); break;
+    case 64: hipLaunchKernelGGL((attn_generic_k<T, 64>), grid, block, 0, s, (const T *)q, (T *)out, (const T *)pool_layer, kg, rm, st, Hq); break;
+    case 96: hipLaunchKernelGGL((attn_generic_k<T, 96>), grid, block, 0, s, (const T *)q, (T *)out, (const T *)pool_layer, kg, rm, st, Hq); break;
+    default: hipLaunchKernelGGL((attn_generic_k<T, 128>), grid, block, 0, s, (const T *)q, (T *)out, (const T *)pool_layer, kg, rm, st, Hq); break;
     }
 }
 
 void launch_attn_generic(hipStream_t s, int dtype, const void *q, void *out, const void *pool_layer, const KvGeom &kg,
-                         const RowMeta &rm, const SeqState &st, int n_q_heads, int D, int max_rows)
+                         const RowMeta &rm, const SeqState &st, int n_q_heads, int max_rows)
 {
-    if (dtype == 0) attn_generic_t<float>(s, q, out, pool_layer, kg, rm, st, n_q_heads, D, max_rows);
-    else attn_generic_t<bf16_t>(s, q, out, pool_layer, kg, rm, st, n_q_heads, D, max_rows);
+    if (dtype == 0) attn_generic_t<float>(s, q, out, pool_layer, kg, rm, st, n_q_heads, max_rows);
+    else attn_generic_t<bf16_t>(s, q, out, pool_layer, kg, rm, st, n_q_heads, max_rows);
 }
 
 // ------------------------------------------------------------------------------------------------ vocabulary reduction

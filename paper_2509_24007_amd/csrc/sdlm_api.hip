@@ -26,6 +26,7 @@ struct Layout {
     size_t l_attn_norm, l_wqkv, l_bqkv, l_wo, l_ffn_norm, l_gate, l_up, l_down, l_size;   // offsets inside a layer
     size_t x, xn, qkv, q, att, act, xhat, logits, conf_rows, ids_rows, attn_part, slabs, lm_part;
     size_t slab_floats, attn_bytes;
+    int verify_rows;
     int group_rows;
     size_t state_ints, meta_ints;
     int max_rows, max_groups, pages_per_seq, n_pages, pool_tiles, prefill_rows;
@@ -87,21 +88,23 @@ void plan(const sdlm_model_cfg *m, const sdlm_run_cfg *r, Layout *L)
     L->l_size = lo;
     L->layer_off.resize(m->n_layers);
     for (int l = 0; l < m->n_layers; ++l) L->layer_off[l] = take(L->l_size);
-    const int max_pos = r->max_seq_len + r->block_D;
+    const int max_pos = r->max_seq_len + 2 * r->block_D;   // a verification input reaches position n + 2D - 3
     L->rope = take((size_t)max_pos * (d / 2) * sizeof(float2));
     L->pages_per_seq = (r->max_seq_len + PAGE - 1) / PAGE;
     L->n_pages = r->kv_layout == 0 ? r->max_batch * L->pages_per_seq : r->n_pages;
-    L->pool_tiles = L->n_pages + r->max_batch;
+    L->pool_tiles = L->n_pages + r->max_batch * r->block_D;   // pages, then one staging tile per sequence and per verification input
     L->pool = take((size_t)m->n_layers * L->pool_tiles * m->n_kv_heads * 2 * PAGE * d * e);
     const int B = r->max_batch, D = r->block_D;
     int pre = r->prefill_rows > 0 ? r->prefill_rows : 2048;
     L->prefill_rows = pre;
+    L->verify_rows = B * ((D - 1) * D + (D - 2) * (D - 1) / 2);
     L->max_rows = B * 2 * D > pre ? B * 2 * D : pre;
+    if (L->verify_rows > L->max_rows) L->max_rows = L->verify_rows;
     L->max_rows = (L->max_rows + 63) / 64 * 64;
     L->max_groups = L->max_rows;   // worst case: every row its own group (prefill of many 1-token prompts)
     L->state_ints = (size_t)B * 3 + (size_t)B * D + (size_t)B * L->pages_per_seq + B + 4 + (size_t)B * D + B;
     L->state_i32 = take(L->state_ints * 4);
-    L->meta_ints = (size_t)L->max_rows * 5 + (size_t)L->max_groups * 3 + (size_t)B * D + 4;
+    L->meta_ints = (size_t)L->max_rows * 7 + (size_t)L->max_groups * 4 + (size_t)B * D + 4;
     L->meta_i32 = take(L->meta_ints * 4);
     const size_t R = L->max_rows;
     L->x = take(R * h * 4);
@@ -238,7 +241,7 @@ void run_layers(sdlm_ctx *c, int rows, int groups)
         {
             Phase p(c, SDLM_PH_ATTN);
             if (c->L.mfma) launch_attn_mfma(s, &c->m, c->r.max_seq_len, c->q, c->att, pool_l, c->kg, c->rm, c->st, c->r.block_D, groups, c->attn_part, c->L.attn_bytes);
-            else launch_attn_generic(s, dt, c->q, c->att, pool_l, c->kg, c->rm, c->st, m.n_q_heads, c->r.block_D, rows);
+            else launch_attn_generic(s, dt, c->q, c->att, pool_l, c->kg, c->rm, c->st, m.n_q_heads, rows);
         }
         run_taps(c, l, 1, c->att, (size_t)rows * nq * e);
         {
@@ -268,6 +271,27 @@ void run_layers(sdlm_ctx *c, int rows, int groups)
             } else launch_gemm_generic(s, dt, EPI_RESID, a);
         }
         run_taps(c, l, 3, c->x, (size_t)rows * h * 4);
+    }
+}
+
+// Final RMSNorm of the rows listed in rm.blk_row, LM head, per-row arg-max and confidence (-> ids_rows, conf_rows).
+void run_lm_head(sdlm_ctx *c, int lm_rows, float *logits)
+{
+    hipStream_t s = c->stream;
+    const int dt = c->m.dtype, h = c->m.hidden, V = c->m.vocab;
+    { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xhat, c->x, c->final_norm, h, c->m.rms_eps, c->rm.blk_row, c->rm.counts + 2, lm_rows, c->slabs, c->pend_slabs, c->pend_stride); c->pend_slabs = 0; }
+    run_taps(c, 0, 4, c->xhat, (size_t)lm_rows * h * c->L.esz);
+    {
+        Phase p(c, SDLM_PH_LMHEAD);
+        if (c->L.mfma) {
+            launch_lmhead_mfma(s, c->xhat, c->lm_head, c->rm.counts + 2, lm_rows, V, h, c->m.logit_scale, c->r.conf_fn, logits, c->lm_part,
+                               c->ids_rows, c->conf_rows);
+        } else {
+            float *z = logits ? logits : c->logits;
+            GemmArgs a{c->xhat, c->lm_head, nullptr, nullptr, z, nullptr, c->rm.counts + 2, lm_rows, V, h, c->m.logit_scale};
+            launch_gemm_generic(s, dt, EPI_LOGITS, a);
+            launch_lm_reduce(s, z, V, c->ids_rows, c->conf_rows, c->r.conf_fn, c->rm.counts + 2, lm_rows);
+        }
     }
 }
 
@@ -334,7 +358,9 @@ int sdlm_create(const sdlm_model_cfg *m, const sdlm_run_cfg *r, void *workspace,
     int32_t *mi = (int32_t *)(ws + L.meta_i32);
     c->rm.tok = mi; mi += L.max_rows; c->rm.pos = mi; mi += L.max_rows; c->rm.seq = mi; mi += L.max_rows;
     c->rm.kind = mi; mi += L.max_rows; c->rm.lim = mi; mi += L.max_rows;
+    c->rm.stg = mi; mi += L.max_rows; c->rm.slim = mi; mi += L.max_rows;
     c->rm.grp_row0 = mi; mi += L.max_groups; c->rm.grp_n = mi; mi += L.max_groups; c->rm.grp_seq = mi; mi += L.max_groups;
+    c->rm.grp_stg = mi; mi += L.max_groups;
     c->rm.blk_row = mi; mi += (size_t)B * D;
     c->rm.counts = mi; mi += 4;
     c->x = (float *)(ws + L.x); c->xn = ws + L.xn; c->qkv = (float *)(ws + L.qkv); c->q = ws + L.q; c->att = ws + L.att;
@@ -344,7 +370,7 @@ int sdlm_create(const sdlm_model_cfg *m, const sdlm_run_cfg *r, void *workspace,
     c->n_ub.assign(B, 0);
     c->info = L.mfma ? "mfma-bf16" : (m->dtype == 0 ? "generic-fp32" : "generic-bf16");
     // rotary table: (cos, sin)(pos * theta^(-2i/d)), evaluated in double on the host
-    const int half = m->head_dim / 2, max_pos = r->max_seq_len + D;
+    const int half = m->head_dim / 2, max_pos = r->max_seq_len + 2 * D;
     std::vector<float2> tab((size_t)max_pos * half);
     for (int i = 0; i < half; ++i) {
         double w = pow((double)m->rope_theta, -2.0 * i / m->head_dim);
@@ -481,6 +507,10 @@ int sdlm_prefill(sdlm_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
             r0 = r1;
         }
         int32_t counts[4] = {R, (int32_t)g0.size(), 0, 0};
+        const std::vector<int32_t> none((size_t)R, -1), zero((size_t)R, 0);   // causal rows: no staging tile
+        HIPCHK(c, hipMemcpyAsync(c->rm.stg, none.data(), R * 4, hipMemcpyHostToDevice, s));
+        HIPCHK(c, hipMemcpyAsync(c->rm.slim, zero.data(), R * 4, hipMemcpyHostToDevice, s));
+        HIPCHK(c, hipMemcpyAsync(c->rm.grp_stg, none.data(), g0.size() * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.tok, tok.data(), R * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.pos, pos.data(), R * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.seq, seq.data(), R * 4, hipMemcpyHostToDevice, s));
@@ -525,26 +555,36 @@ int sdlm_decode_step(sdlm_ctx *c, int32_t *ids, int32_t *count, float *conf, flo
     }
     hipStream_t s = c->stream;
     const int rows = B * 2 * D;
-    { Phase p(c, SDLM_PH_ROWS); launch_assemble_decode(s, c->st, c->rm, B, D, c->m.mask_token_id, c->L.group_rows); }
+    { Phase p(c, SDLM_PH_ROWS); launch_assemble_decode(s, c->st, c->rm, B, D, c->m.mask_token_id, c->L.group_rows, c->kg.staging_base); }
     run_layers(c, rows, B * ((2 * D + c->L.group_rows - 1) / c->L.group_rows));
-    const int dt = c->m.dtype, h = c->m.hidden, V = c->m.vocab;
-    { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xhat, c->x, c->final_norm, h, c->m.rms_eps, c->rm.blk_row, c->rm.counts + 2, B * D, c->slabs, c->pend_slabs, c->pend_stride); c->pend_slabs = 0; }
-    run_taps(c, 0, 4, c->xhat, (size_t)B * D * h * c->L.esz);
-    {
-        Phase p(c, SDLM_PH_LMHEAD);
-        if (c->L.mfma) {
-            launch_lmhead_mfma(s, c->xhat, c->lm_head, c->rm.counts + 2, B * D, V, h, c->m.logit_scale, c->r.conf_fn, logits, c->lm_part,
-                               c->ids_rows, c->conf_rows);
-        } else {
-            float *z = logits ? logits : c->logits;
-            GemmArgs a{c->xhat, c->lm_head, nullptr, nullptr, z, nullptr, c->rm.counts + 2, B * D, V, h, c->m.logit_scale};
-            launch_gemm_generic(s, dt, EPI_LOGITS, a);
-            launch_lm_reduce(s, z, V, c->ids_rows, c->conf_rows, c->r.conf_fn, c->rm.counts + 2, B * D);
-        }
-    }
+    run_lm_head(c, B * D, logits);
     { Phase p(c, SDLM_PH_ACCEPT); launch_accept(s, c->st, c->ids_rows, c->conf_rows, B, D, c->r.tau, c->r.accept_rule, ids, count, conf); }
     HIPCHK(c, hipGetLastError());
     c->stepped = true;
+    return SDLM_OK;
+}
+
+int sdlm_verify_step(sdlm_ctx *c, int32_t rule, int32_t *ids_tilde, int32_t *count, float *logits)
+{
+    if (!c) return SDLM_EINVAL;
+    if (!c->stepped) return fail(c, SDLM_ESTATE, "verify_step without a preceding decode_step");
+    if (rule != 0 && rule != 1) return fail(c, SDLM_EINVAL, "verify rule %d is not 0 (agreeing prefix) or 1 (largest agreeing index)", rule);
+    const int B = c->batch, D = c->r.block_D;
+    if (2 * D - 2 > PAGE) return fail(c, SDLM_EINVAL, "verification needs 2D-2 <= %d staging slots; block_D is %d", PAGE, D);
+    hipStream_t s = c->stream;
+    if (D >= 2) {
+        // positions reach n + 2D - 3 <= max_seq_len + D - 2 (decode_step checked n + D - 1 <= max_seq_len): inside the rotary
+        // table; no cache slot beyond n - 1 is touched
+        const int rows = B * ((D - 1) * D + (D - 2) * (D - 1) / 2);
+        const int gr = c->L.group_rows;
+        int groups = 0;
+        for (int j = 2; j <= D; ++j) groups += (j - 2 + D + gr - 1) / gr;
+        { Phase p(c, SDLM_PH_ROWS); launch_assemble_verify(s, c->st, c->rm, B, D, c->m.mask_token_id, gr, c->kg.staging_base); }
+        run_layers(c, rows, B * groups);
+        run_lm_head(c, B * (D - 1), logits);
+    }
+    { Phase p(c, SDLM_PH_ACCEPT); launch_verify_accept(s, c->st, c->ids_rows, B, D, rule, ids_tilde, count); }
+    HIPCHK(c, hipGetLastError());
     return SDLM_OK;
 }
 

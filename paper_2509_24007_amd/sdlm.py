@@ -19,7 +19,7 @@ PHASES = ("rows", "norm", "qkv", "rope", "attn", "oproj", "gateup", "down", "lmh
 OK, EINVAL, ECAPACITY, ESTATE, EHIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("sdlm_workspace_bytes", "sdlm_create", "sdlm_init_weights", "sdlm_prefill", "sdlm_decode_step",
-           "sdlm_kv_commit", "sdlm_get_lengths", "sdlm_debug_tap", "sdlm_debug_rows", "sdlm_debug_read_kv",
+           "sdlm_verify_step", "sdlm_kv_commit", "sdlm_get_lengths", "sdlm_debug_tap", "sdlm_debug_rows", "sdlm_debug_read_kv",
            "sdlm_max_rows", "sdlm_profile", "sdlm_profile_read", "sdlm_kernel_info", "sdlm_last_error",
            "sdlm_destroy")
 
@@ -69,6 +69,8 @@ def load():
     L.sdlm_prefill.argtypes = [vp, i32, vp, vp]
     L.sdlm_decode_step.restype = C.c_int
     L.sdlm_decode_step.argtypes = [vp, vp, vp, vp, vp]
+    L.sdlm_verify_step.restype = C.c_int
+    L.sdlm_verify_step.argtypes = [vp, C.c_int32, vp, vp, vp]
     L.sdlm_kv_commit.restype = C.c_int
     L.sdlm_kv_commit.argtypes = [vp, vp, vp]
     L.sdlm_get_lengths.restype = C.c_int
@@ -226,6 +228,18 @@ class Context:
         assert logits is None or (logits.dtype == torch.float32 and logits.numel() >= B * D * self.m.vocab and
                                   logits.is_cuda and logits.is_contiguous())
         self._check(self.L.sdlm_decode_step(self.h, _dp(ids), _dp(count), _dp(conf), _dp(logits)))
+
+    def verify_step(self, rule: int = 0, ids_tilde: Optional[torch.Tensor] = None, count: Optional[torch.Tensor] = None,
+                    logits: Optional[torch.Tensor] = None) -> None:
+        """Self-speculative verification of the last decode_step; ids_tilde [batch, D] int32, count [batch] int32,
+        logits [batch, D-1, vocab] fp32 (all optional, on the device)."""
+        for t, n in ((ids_tilde, self.batch * self.D), (count, self.batch)):
+            if t is not None:
+                assert t.dtype == torch.int32 and t.is_cuda and t.is_contiguous() and t.numel() >= n
+        if logits is not None:
+            assert logits.dtype == torch.float32 and logits.is_cuda and logits.is_contiguous()
+            assert logits.numel() >= self.batch * (self.D - 1) * self.m.vocab
+        self._check(self.L.sdlm_verify_step(self.h, int(rule), _dp(ids_tilde), _dp(count), _dp(logits)))
 
     def kv_commit(self, ids_override: Optional[torch.Tensor] = None, count_override: Optional[torch.Tensor] = None) -> None:
         if ids_override is not None:

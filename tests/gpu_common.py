@@ -49,12 +49,16 @@ class Stats:
 
 
 def lockstep(ctx, om, prompts, D, tau, steps, *, logit_tol, conf_tol, conf_fn=0, rule=0, overrides=None,
-             tie_gap=1e-3, bf16=False, check_logits=True, max_len=None, om_exact=None, exact_tol=2e-2):
+             tie_gap=1e-3, bf16=False, check_logits=True, max_len=None, om_exact=None, exact_tol=2e-2, verify_rule=None):
     """Run the HIP library and one oracle sequence per prompt step by step on the same token history.
 
     After every step both sides commit the same tokens: the seeded override tokens on steps where `overrides`
     supplies them, otherwise the oracle's own accepted prefix (through the library's NULL commit when the two
     agree, through the override arguments otherwise).  Returns Stats; asserts the parity bar.
+
+    With `verify_rule` (0 or 1) every step is a self-speculative one: after the step the library's verification pass
+    runs and is compared with the oracle's (logits of every verification input, ytilde, gamma_verify), and the
+    verified count is what gets committed.
 
     `om` may be the oracle with the bf16 rounding-point model switched on; `om_exact`, if given, is the plain
     fp64 oracle run alongside on the same tokens: the library's logits must also stay within `exact_tol`
@@ -75,8 +79,17 @@ def lockstep(ctx, om, prompts, D, tau, steps, *, logit_tol, conf_tol, conf_fn=0,
     conf = torch.empty(B, D, dtype=torch.float32, device="cuda")
     logits = torch.empty(B * D, V, dtype=torch.float32, device="cuda") if check_logits else None
     st = Stats()
+    if verify_rule is not None:
+        v_ids = torch.empty(B, D, dtype=torch.int32, device="cuda")
+        v_cnt = torch.empty(B, dtype=torch.int32, device="cuda")
+        v_log = torch.empty(B, max(D - 1, 1), V, dtype=torch.float32, device="cuda")
+        st.verify_rows = st.verify_skipped = st.verify_near_tie = 0
+        st.verify_gammas = []
     for t in range(steps):
         ctx.decode_step(ids, cnt, conf, logits)
+        if verify_rule is not None:
+            v_log.fill_(float("nan"))
+            ctx.verify_step(verify_rule, v_ids, v_cnt, v_log)
         torch.cuda.synchronize()
         g_ids, g_cnt, g_conf = ids.cpu().numpy(), cnt.cpu().numpy(), conf.cpu().numpy()
         g_log = logits.cpu().numpy().reshape(B, D, V) if check_logits else None
@@ -123,6 +136,34 @@ def lockstep(ctx, om, prompts, D, tau, steps, *, logit_tol, conf_tol, conf_fn=0,
                     e = float(np.max(np.abs(g_log[b, k] - lx[k])) / np.max(np.abs(lx[k])))
                     st.exact_errs.append(e)
                     assert e <= exact_tol, f"step {t} seq {b} row {k}: {e:.3e} from the exact oracle (> {exact_tol})"
+        if verify_rule is not None:
+            gv_ids, gv_cnt, gv_log = v_ids.cpu().numpy(), v_cnt.cpu().numpy(), v_log.cpu().numpy()
+            for b in range(B):
+                # the library's gamma_verify is Eq. 10 applied to its own tokens, bit for bit
+                assert int(gv_cnt[b]) == orc.gamma_verify(g_ids[b], gv_ids[b], verify_rule)
+                assert gv_ids[b, 0] == g_ids[b, 0]
+                yt, gv, zl = seqs[b].verify(verify_rule, want_logits=True)
+                o_cnt[b] = gv
+                st.verify_gammas.append(gv)
+                if not np.array_equal(g_ids[b], o_ids[b]):
+                    st.verify_skipped += 1      # the speculative tokens already differ at a near tie: inputs differ
+                    agree = False
+                    continue
+                for j in range(2, D + 1):
+                    st.verify_rows += 1
+                    zo, zg = zl[j - 1], gv_log[b, j - 2]
+                    zmax = np.max(np.abs(zo))
+                    err_abs = float(np.max(np.abs(zg - zo)))
+                    st.max_logit_err = max(st.max_logit_err, err_abs / zmax)
+                    assert err_abs / zmax <= logit_tol, f"step {t} seq {b} verify input {j}: logit rel err {err_abs / zmax:.3e}"
+                    if gv_ids[b, j - 1] != yt[j - 1]:
+                        srt = np.sort(zo)
+                        band = max(tie_gap, 2.0 * err_abs) if bf16 else tie_gap
+                        assert srt[-1] - srt[-2] < band, f"step {t} seq {b} verify input {j}: id {gv_ids[b, j - 1]} vs {yt[j - 1]}"
+                        st.verify_near_tie += 1
+                        agree = False
+                if np.array_equal(gv_ids[b], yt):
+                    assert int(gv_cnt[b]) == gv
         if overrides is not None and t < overrides[0].shape[0] and t % 2 == 1:
             c_ids, c_cnt = overrides[0][t, :B].numpy().astype(np.int32), overrides[1][t, :B].numpy().astype(np.int32)
             use_null = False

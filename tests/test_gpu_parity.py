@@ -265,3 +265,95 @@ def test_bf16_mfma_entropy_confidence():
     st, _ = lockstep(ctx, om, prompts, 4, 0.05, 4, logit_tol=2e-2, conf_tol=1e-3, conf_fn=1, bf16=True)
     print(st)
     ctx.close()
+
+
+# ------------------------------------------------------------------ self-speculative verification (Sec. 3.4, Eq. 10)
+@pytest.mark.parametrize("D,rule,paged", [(2, 0, False), (4, 0, True), (4, 1, False), (6, 0, True), (9, 1, False)])
+def test_verify_small_fp32(D, rule, paged):
+    """Second pass of a self-speculative step against the oracle's: logits of every verification input, ytilde,
+    gamma_verify bit-exact, and the verified count is what an argument-less commit publishes."""
+    m = gpu_cfg()
+    om, g_dev, layers_dev = both_models(m, seed=6, std=0.3)
+    lens = [1, 2, 15, 16, 17, 33]
+    prompts = [syn.uniform_int(D, f"v{i}", n, 0, m.vocab - 1).numpy() for i, n in enumerate(lens)]
+    steps = 5
+    ovr = syn.make_overrides(10, steps, len(lens), D, m.vocab)
+    max_len = max(lens) + steps * D + D
+    n_pages = sum((n + steps * D + 15) // 16 + 1 for n in lens)
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=len(lens), max_seq_len=max_len, D=D, tau=0.5, paged=paged, n_pages=n_pages,
+                      prefill_rows=64)
+    st, _ = lockstep(ctx, om, prompts, D, 0.5, steps, logit_tol=1e-4, conf_tol=1e-5, overrides=ovr, max_len=max_len,
+                     verify_rule=rule)
+    print(f"verify D={D} rule={rule}", st, "verify rows", st.verify_rows, "gammas", np.bincount(st.verify_gammas))
+    assert st.verify_rows == steps * len(lens) * (D - 1) and st.verify_skipped == 0 and st.verify_near_tie == 0
+    ctx.close()
+
+
+def test_verify_position_independent_model_accepts_whole_block():
+    """All-zero weights: every logit row is constant, arg-max is token 0 everywhere, so every position verifies."""
+    m = gpu_cfg()
+    om, g_dev, layers_dev = both_models(m, seed=6, std=0.0)
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=2, max_seq_len=64, D=4, tau=2.0)
+    ctx.prefill([np.array([4, 2, 7], dtype=np.int32), np.array([1], dtype=np.int32)])
+    ids = torch.empty(2, 4, dtype=torch.int32, device="cuda")
+    cnt = torch.empty(2, dtype=torch.int32, device="cuda")
+    vid = torch.empty(2, 4, dtype=torch.int32, device="cuda")
+    vc = torch.empty(2, dtype=torch.int32, device="cuda")
+    ctx.decode_step(ids, cnt)
+    ctx.verify_step(0, vid, vc)
+    torch.cuda.synchronize()
+    assert cnt.tolist() == [1, 1] and vc.tolist() == [4, 4]
+    assert ids.cpu().eq(0).all() and vid.cpu().eq(0).all()
+    ctx.kv_commit()
+    n, c = ctx.get_lengths()
+    assert n.tolist() == [3 + 4, 1 + 4]
+    ctx.close()
+
+
+def test_verify_error_paths():
+    m = gpu_cfg()
+    om, g_dev, layers_dev = both_models(m, seed=6, std=0.3)
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=1, max_seq_len=64, D=4, tau=0.5)
+    ctx.prefill([np.array([1, 2, 3], dtype=np.int32)])
+    from paper_2509_24007_amd.sdlm import SdlmError
+    with pytest.raises(SdlmError):
+        ctx.verify_step(0)              # no step yet
+    ids = torch.empty(1, 4, dtype=torch.int32, device="cuda")
+    cnt = torch.empty(1, dtype=torch.int32, device="cuda")
+    ctx.decode_step(ids, cnt)
+    with pytest.raises(SdlmError):
+        ctx.verify_step(2)              # unknown rule
+    ctx.verify_step(0)
+    ctx.verify_step(1)                  # may be repeated before the commit
+    ctx.kv_commit()
+    with pytest.raises(SdlmError):
+        ctx.verify_step(0)              # the step has been committed
+    ctx.close()
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=1, max_seq_len=96, D=10, tau=0.5)
+    ctx.prefill([np.array([1, 2, 3], dtype=np.int32)])
+    ids = torch.empty(1, 10, dtype=torch.int32, device="cuda")
+    ctx.decode_step(ids, cnt)
+    with pytest.raises(SdlmError):
+        ctx.verify_step(0)              # 2D-2 staging slots do not fit a 16-slot tile
+    ctx.close()
+
+
+@pytest.mark.parametrize("name,kw,lens,D", [
+    ("vg2", {}, [1, 9, 40, 100], 4),
+    ("vg7", dict(n_q_heads=14, n_kv_heads=2, vocab=1000, ffn=320), [3, 17, 33, 64, 70], 4),
+    ("vg8-D8-two-groups-per-input", dict(n_q_heads=16, n_kv_heads=2, hidden=512), [5, 130, 300], 8),
+])
+def test_verify_bf16_mfma(name, kw, lens, D):
+    m = mfma_cfg(**kw)
+    om, g_dev, layers_dev = both_models(m, seed=21, std=0.05)
+    prompts = [syn.uniform_int(D, f"{name}{i}", n, 0, m.vocab - 1).numpy() for i, n in enumerate(lens)]
+    steps = 4
+    max_len = max(lens) + steps * D + D
+    n_pages = sum((n + steps * D + 15) // 16 + 1 for n in lens)
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=len(lens), max_seq_len=max_len, D=D, tau=0.6, paged=True, n_pages=n_pages,
+                      prefill_rows=128)
+    assert ctx.kernel_info == "mfma-bf16"
+    st, _ = lockstep(ctx, om, prompts, D, 0.6, steps, logit_tol=2e-2, conf_tol=1e-3, bf16=True, max_len=max_len, verify_rule=0)
+    print(name, st, "verify rows", st.verify_rows, "skipped", st.verify_skipped, "near ties", st.verify_near_tie)
+    assert st.verify_rows > 0
+    ctx.close()
