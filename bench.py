@@ -50,6 +50,9 @@ def parse():
                     help="phases bracketed by HIP events inside the timed region: one phase name (default: the dominant kernel), "
                          "main (all six big kernels, ~6%% slower steps) or none; the per-kernel table of the other phases comes "
                          "from up to 32 extra untimed steps")
+    ap.add_argument("--verify", type=int, default=None, choices=(0, 1),
+                    help="self-speculative decoding: every step is followed by the verification pass and commits gamma_verify "
+                         "tokens (rule 0: agreeing prefix, 1: largest agreeing index); no per-kernel table in this mode")
     ap.add_argument("--profile-all", action="store_true", help="bracket every phase with events (adds overhead)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one plain 1 GiB device copy first: under rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE give the counter scale")
@@ -87,7 +90,7 @@ def algorithmic_bytes(m, esz, lens_sum, R):
     return weights, kv
 
 
-def run_tau(ctx, m, r, prompts, tau_idx, steps, warmup, prof_phases, table_steps=0):
+def run_tau(ctx, m, r, prompts, tau_idx, steps, warmup, prof_phases, table_steps=0, verify=None):
     """Warm-up, then the timed region (only `prof_phases` carry events: every bracketed phase costs two event records
     per launch), then `table_steps` untimed extra steps with every main phase bracketed for the per-kernel table."""
     import torch
@@ -96,15 +99,18 @@ def run_tau(ctx, m, r, prompts, tau_idx, steps, warmup, prof_phases, table_steps
     torch.cuda.synchronize()
     ids = torch.zeros(warmup + steps + table_steps, B, D, dtype=torch.int32, device="cuda")
     cnt = torch.zeros(warmup + steps + table_steps, B, dtype=torch.int32, device="cuda")
-    for t in range(warmup):
+    def one(t):
         ctx.decode_step(ids[t], cnt[t])
+        if verify is not None:
+            ctx.verify_step(verify, None, cnt[t])      # the committed count becomes gamma_verify
         ctx.kv_commit()
+    for t in range(warmup):
+        one(t)
     torch.cuda.synchronize()
     ctx.profile(prof_phases)
     t0 = time.perf_counter()
     for t in range(warmup, warmup + steps):
-        ctx.decode_step(ids[t], cnt[t])
-        ctx.kv_commit()
+        one(t)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     phases = ctx.profile_read()
@@ -112,8 +118,7 @@ def run_tau(ctx, m, r, prompts, tau_idx, steps, warmup, prof_phases, table_steps
     if table_steps:
         ctx.profile(MAIN_PHASES)
         for t in range(warmup + steps, warmup + steps + table_steps):
-            ctx.decode_step(ids[t], cnt[t])
-            ctx.kv_commit()
+            one(t)
         torch.cuda.synchronize()
         table = ctx.profile_read()
     ctx.profile(None)
@@ -169,7 +174,7 @@ def main():
     taus = [tau] + ([t for t in (r.taus or []) if t != tau] if a.sweep else [])
     B, D = r.batch, r.block_D
     prompts = [p.numpy() for p in syn.make_prompts(wl.seed, B, r.prompt_lo, r.prompt_hi, m.vocab)]
-    table_steps = 0 if (a.profile_all or a.phases == "main") else min(32, a.steps)
+    table_steps = 0 if (a.profile_all or a.phases == "main" or a.verify is not None) else min(32, a.steps)
     total_steps = a.warmup + a.steps + table_steps
     max_len = max(len(p) for p in prompts) + total_steps * D + D
     n_pages = sum((len(p) + total_steps * D + D + 15) // 16 + 1 for p in prompts) if r.paged else 0
@@ -180,6 +185,8 @@ def main():
     host_g, host_layers = build_model(ctx, m, wl.seed, keep_host_layers=m.n_layers if want_cpu else None)
     t_build = time.perf_counter() - t0
     prof = True if a.profile_all else {"main": MAIN_PHASES, "none": None}.get(a.phases, (a.phases,))
+    if a.verify is not None:
+        prof = None
     esz = 4 if m.dtype == "fp32" else 2
     results = []
     for ti, tv in enumerate(taus):
@@ -188,7 +195,7 @@ def main():
             ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=B, max_seq_len=max_len, block_D=D, tau=tv, paged=r.paged, n_pages=n_pages)
             build_model(ctx, m, wl.seed)
         t0 = time.perf_counter()
-        dt, cnt, phases, n_end, tphases = run_tau(ctx, m, r, prompts, ti, a.steps, a.warmup, prof, table_steps if ti == 0 else 0)
+        dt, cnt, phases, n_end, tphases = run_tau(ctx, m, r, prompts, ti, a.steps, a.warmup, prof, table_steps if ti == 0 else 0, a.verify)
         t_total = time.perf_counter() - t0
         timed = cnt[a.warmup:a.warmup + a.steps].numpy().astype(np.int64)
         accepted = int(timed.sum())
@@ -258,7 +265,9 @@ def main():
         "dtype": "f32" if m.dtype == "fp32" else "bf16",
         "data": "synthetic",
         "config": {"workload": wl.name, "batch": B, "block_D": D, "tau": main_r["tau"], "paged_kv": bool(r.paged),
-                   "prompt_len": [r.prompt_lo, r.prompt_hi], "kernels": ctx.kernel_info},
+                   "prompt_len": [r.prompt_lo, r.prompt_hi], "kernels": ctx.kernel_info,
+                   "decoding": "greedy longest-prefix (gamma_tau)" if a.verify is None else
+                               "self-speculative (gamma_verify, rule %d): a step is the block step plus the verification pass" % a.verify},
         "gamma_hist": main_r["hist"],
         "tokens_per_step_per_seq": main_r["accepted"] / (a.steps * B),
         "rows_per_step": main_r["R_mean"],
@@ -270,6 +279,10 @@ def main():
         "kernels": {k: {kk: (round(vv, 3) if isinstance(vv, float) else vv) for kk, vv in v.items()} for k, v in table.items()},
         "setup_s": {"weights": round(t_build, 1), "prefill_and_run": round(main_r["t_total"], 1)},
     }
+    if a.verify is not None:    # the byte accounting above describes the block step alone
+        for k in ("step_algorithmic_GB", "step_hbm_GBs", "step_hbm_frac", "roofline"):
+            out[k] = None
+        out["verify_rows_per_step"] = B * ((D - 1) * D + (D - 2) * (D - 1) // 2)
     if len(results) > 1:
         out["tau_sweep"] = [dict(tau=x["tau"], value=x["accepted"] / x["dt"], ms_per_step=1e3 * x["dt"] / a.steps,
                                  gamma_hist=x["hist"]) for x in results]

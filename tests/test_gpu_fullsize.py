@@ -261,3 +261,102 @@ def test_c2_shape_fp32_debug_mode():
     print("C2-fp32", st)
     assert st.id_near_tie == 0
     ctx.close()
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("name", ["C3", "C4"])
+def test_fullsize_verify_is_the_next_steps_first_prediction(name):
+    """Self-speculative verification at full size (Sec. 3.4): by its definition ytilde^j is what an ordinary block
+    step predicts first once yhat^1..yhat^{j-1} have been appended.  The verification pass computes it from rows that
+    live in staging tiles; here the same quantity is produced the long way (commit j-1 speculative tokens, run a real
+    step, read its block rows) with j spread over the batch.  Checked: the verification rows (integers, exact); the
+    first layer's attention output of every block row of the chosen inputs against the real step's (same inputs, so
+    only summation order and one bf16 rounding differ); and the final logits, where two bf16 passes whose roundings
+    have decorrelated over the layers differ by about sqrt(2) times the depth's noise floor.  The real step is the
+    path the stage-wise test above pins to the oracle."""
+    wl = syn.workloads()[name]
+    m, r = wl.model, wl.run
+    B, D, V = r.batch, r.block_D, m.vocab
+    nq = m.n_q_heads * m.head_dim
+    prompts = [p.numpy() for p in syn.make_prompts(wl.seed, B, r.prompt_lo, r.prompt_hi, V)]
+    max_len = max(len(p) for p in prompts) + 4 * D
+    n_pages = sum((len(p) + 4 * D + 15) // 16 + 1 for p in prompts) if r.paged else 0
+    ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=B, max_seq_len=max_len, block_D=D, tau=r.tau, paged=r.paged, n_pages=n_pages,
+                       poison=True)
+    load_streaming(ctx, m, wl.seed)
+    ctx.prefill(prompts)
+    ids = torch.empty(B, D, dtype=torch.int32, device="cuda")
+    cnt = torch.empty(B, dtype=torch.int32, device="cuda")
+    ctx.decode_step(ids, cnt)
+    ctx.kv_commit()                                   # the checked step then has pending rows
+    n0, _ = ctx.get_lengths()
+    n0 = n0.numpy()
+    yhat = torch.empty(B, D, dtype=torch.int32, device="cuda")
+    ytil = torch.empty(B, D, dtype=torch.int32, device="cuda")
+    gv = torch.empty(B, dtype=torch.int32, device="cuda")
+    vlog = torch.full((B, D - 1, V), float("nan"), dtype=torch.float32, device="cuda")
+    ctx.decode_step(yhat, cnt)
+    att_v = torch.zeros(ctx.max_rows, nq, dtype=torch.bfloat16, device="cuda")
+    ctx.tap(0, 1, att_v)
+    ctx.verify_step(0, ytil, gv, vlog)
+    torch.cuda.synchronize()
+    ctx.tap(0, -1, None)
+    yh, yt, g = yhat.cpu().numpy(), ytil.cpu().numpy(), gv.cpu().numpy()
+    # --- the verification rows: for every sequence and input j = 2..D: yhat^1..yhat^{j-2} causal, then [yhat^{j-1}, m..]
+    vrows = ctx.rows()
+    rows_seq = (D - 1) * D + (D - 2) * (D - 1) // 2
+    assert len(vrows["tok"]) == B * rows_seq
+    first_row = {}
+    r0 = 0
+    for b in range(B):
+        for j in range(2, D + 1):
+            want_tok = [int(x) for x in yh[b, : j - 2]] + [int(yh[b, j - 2])] + [m.mask_token_id] * (D - 1)
+            want_pos = list(range(n0[b], n0[b] + j - 2)) + list(range(n0[b] + j - 2, n0[b] + j - 2 + D))
+            k = j - 2 + D
+            assert vrows["tok"][r0:r0 + k].tolist() == want_tok and vrows["pos"][r0:r0 + k].tolist() == want_pos
+            assert vrows["seq"][r0:r0 + k].eq(b).all() and vrows["kind"][r0:r0 + k].tolist() == list(range(k))
+            first_row[(b, j)] = r0 + j - 2
+            r0 += k
+    assert np.array_equal(yt[:, 0], yh[:, 0])
+    for b in range(B):
+        assert int(g[b]) == orc.gamma_verify(yh[b], yt[b], 0)
+    assert np.array_equal(vlog.argmax(dim=2).cpu().numpy(), yt[:, 1:])      # ytilde is the arg-max of the returned logits
+    # --- the long way: commit j_b - 1 speculative tokens of sequence b, j_b cycling over 2..D, and run a real step
+    j_of = np.array([2 + (b % (D - 1)) for b in range(B)])
+    ctx.kv_commit(yhat, torch.tensor(j_of - 1, dtype=torch.int32).cuda())
+    nxt = torch.empty(B, D, dtype=torch.int32, device="cuda")
+    logits = torch.empty(B * D, V, dtype=torch.float32, device="cuda")
+    att_r = torch.zeros(ctx.max_rows, nq, dtype=torch.bfloat16, device="cuda")
+    ctx.tap(0, 1, att_r)
+    ctx.decode_step(nxt, cnt, None, logits)
+    torch.cuda.synchronize()
+    ctx.tap(0, -1, None)
+    rrows = ctx.rows()
+    att_errs = []
+    r0 = 0
+    for b in range(B):
+        p = int(j_of[b]) - 1
+        assert rrows["kind"][r0 + p:r0 + p + D].tolist() == list(range(D))
+        a_real = f64(att_r[r0 + p:r0 + p + D])
+        fv = first_row[(b, int(j_of[b]))]
+        a_ver = f64(att_v[fv:fv + D])
+        att_errs.append(vec_err(a_ver, a_real))
+        r0 += p + D
+    first = logits.view(B, D, V)[:, 0].cpu().numpy().astype(np.float64)
+    vl = vlog.cpu().numpy().astype(np.float64)
+    errs, ties = [], 0
+    for b in range(B):
+        zv, zr = vl[b, j_of[b] - 2], first[b]
+        err = float(np.max(np.abs(zv - zr)))
+        errs.append(err / np.max(np.abs(zr)))
+        if yt[b, j_of[b] - 1] != nxt[b, 0].item():
+            srt = np.sort(zr)
+            assert srt[-1] - srt[-2] < 2 * err, f"seq {b} input {j_of[b]}: {yt[b, j_of[b] - 1]} vs {nxt[b, 0].item()}"
+            ties += 1
+    noise = 1.1e-3 * np.sqrt(6 * m.n_layers)          # one bf16 pass against exact arithmetic, measured on this design
+    print(name, "verify vs real next step: layer-0 attention max rel diff %.3e; logits max rel diff %.3e median %.3e "
+          "(single-pass noise floor %.2e), near ties %d, gamma_verify hist %s"
+          % (max(att_errs), max(errs), float(np.median(errs)), noise, ties, np.bincount(g, minlength=D + 1)[1:].tolist()))
+    assert max(att_errs) <= 1e-2
+    assert float(np.median(errs)) <= 2.0 * noise and max(errs) <= 3.0 * noise
+    ctx.close()
