@@ -29,7 +29,8 @@ def build(force: bool = False) -> str:
 class _Cfg(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "hidden", "n_q_heads", "n_kv_heads", "head_dim", "ffn",
                                          "vocab", "mask_token_id", "has_qkv_bias", "wdtype")] + \
-               [(n, C.c_double) for n in ("rope_theta", "rms_eps", "logit_scale")] + [("bf16_points", C.c_int32)]
+               [(n, C.c_double) for n in ("rope_theta", "rms_eps", "logit_scale")] + [("bf16_points", C.c_int32),
+                                                                                     ("block_causal", C.c_int32)]
 
 
 _PP = C.POINTER(C.c_void_p)
@@ -61,7 +62,7 @@ def lib():
         L.orc_gamma.restype = i32
         L.orc_gamma.argtypes = [vp, i32, f32, i32]
         L.orc_block_mask.restype = None
-        L.orc_block_mask.argtypes = [vp, i32, i32]
+        L.orc_block_mask.argtypes = [vp, i32, i32, i32]
         L.orc_forward_masked_logits.restype = C.c_int
         L.orc_forward_masked_logits.argtypes = [vp, vp, vp, i32, vp, i32, i32, vp]
         L.orc_brute_step.restype = C.c_int
@@ -132,7 +133,8 @@ class Model:
 
     def __init__(self, *, n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab,
                  rope_theta, rms_eps, logit_scale, mask_token_id, has_qkv_bias,
-                 globals_: Dict[str, object], layers: Sequence[Dict[str, object]], bf16_points: bool = False):
+                 globals_: Dict[str, object], layers: Sequence[Dict[str, object]], bf16_points: bool = False,
+                 block_causal: bool = False):
         self.vocab, self.hidden, self.n_layers = vocab, hidden, n_layers
         self.head_dim, self.n_kv_heads, self.n_q_heads = head_dim, n_kv_heads, n_q_heads
         self._keep: List[np.ndarray] = []
@@ -140,7 +142,8 @@ class Model:
         wdtype = 0 if emb.dtype == np.float32 else 1
         self.wdtype = wdtype
         self.cfg = _Cfg(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, vocab, mask_token_id,
-                        int(bool(has_qkv_bias)), wdtype, rope_theta, rms_eps, logit_scale, int(bool(bf16_points)))
+                        int(bool(has_qkv_bias)), wdtype, rope_theta, rms_eps, logit_scale, int(bool(bf16_points)),
+                        int(bool(block_causal)))
         self.w = _Weights()
         self.arrays: Dict[str, object] = {}
         for name in ("embed", "lm_head", "final_norm"):
@@ -186,7 +189,8 @@ def model_from_inputs(mcfg, globals_, layers, bf16_points: bool = False) -> Mode
     return Model(n_layers=mcfg.n_layers, hidden=mcfg.hidden, n_q_heads=mcfg.n_q_heads, n_kv_heads=mcfg.n_kv_heads,
                  head_dim=mcfg.head_dim, ffn=mcfg.ffn, vocab=mcfg.vocab, rope_theta=mcfg.rope_theta,
                  rms_eps=mcfg.rms_eps, logit_scale=mcfg.logit_scale, mask_token_id=mcfg.mask_token_id,
-                 has_qkv_bias=mcfg.has_qkv_bias, globals_=globals_, layers=layers, bf16_points=bf16_points)
+                 has_qkv_bias=mcfg.has_qkv_bias, globals_=globals_, layers=layers, bf16_points=bf16_points,
+                 block_causal=getattr(mcfg, "block_causal", False))
 
 
 def _i32(a) -> np.ndarray:
@@ -225,10 +229,10 @@ def gamma_verify(yhat, ytilde, rule: int = 0) -> int:
     return int(lib().orc_gamma_verify(_ptr(a), _ptr(b), a.size, rule))
 
 
-def block_mask(n: int, D: int) -> np.ndarray:
+def block_mask(n: int, D: int, causal: bool = False) -> np.ndarray:
     T = n + D - 1
     m = np.zeros((T, T), dtype=np.uint8)
-    lib().orc_block_mask(_ptr(m), n, D)
+    lib().orc_block_mask(_ptr(m), n, D, int(bool(causal)))
     return m
 
 

@@ -55,6 +55,7 @@ typedef struct {
     int32_t wdtype;              /* 0: float32 arrays, 1: bf16 bit patterns (uint16) */
     double rope_theta, rms_eps, logit_scale;
     int32_t bf16_points;         /* 1: round activations to bf16 at the points where a bf16 pipeline does (see round_rows) */
+    int32_t block_causal;        /* 1: the ablation of Sec. 4.4 "Causal Attention": causal instead of mutual attention inside the block */
 } orc_cfg;
 
 typedef struct {
@@ -361,13 +362,16 @@ int orc_forward_masked_logits(const orc_cfg *c, const orc_weights *w, const int3
     return 0;
 }
 
-/* The inference mask for known length n and block size D: T = n + D - 1, block start s = n - 1. */
-void orc_block_mask(uint8_t *mask, int32_t n, int32_t D)
+/*
+ * The inference mask for known length n and block size D: T = n + D - 1, block start s = n - 1.
+ * causal != 0 gives the ablation's variant: the block's rows attend causally too, i.e. the plain lower triangle.
+ */
+void orc_block_mask(uint8_t *mask, int32_t n, int32_t D, int32_t causal)
 {
     int T = n + D - 1, s = n - 1;
     for (int u = 0; u < T; ++u)
         for (int v = 0; v < T; ++v)
-            mask[(size_t)u * T + v] = (uint8_t)((v <= u) || (u >= s && v >= s));
+            mask[(size_t)u * T + v] = (uint8_t)((v <= u) || (!causal && u >= s && v >= s));
 }
 
 /*
@@ -384,7 +388,7 @@ int orc_brute_step(const orc_cfg *c, const orc_weights *w, const int32_t *tokens
     uint8_t *mask = malloc((size_t)T * T);
     for (int i = 0; i < n; ++i) u[i] = tokens[i];
     for (int i = n; i < T; ++i) u[i] = c->mask_token_id;
-    orc_block_mask(mask, n, D);
+    orc_block_mask(mask, n, D, c->block_causal);
     double *logits = logits_out ? logits_out : malloc(sizeof(double) * (size_t)D * c->vocab);
     orc_forward_masked_logits(c, w, u, T, mask, n - 1, D, logits);
     decide(logits, c, D, tau, rule, conf_fn, ids, conf, gamma);
@@ -521,7 +525,8 @@ static int seq_forward(orc_seq *s, int n_block, double *logits_out)
             /* visible cache keys: causal row at position q sees [0, q]; a block row sees
                [0, s) (not the causal copy of x_last at s) and then the D block keys */
             int n_cache = is_block ? st : pos[r] + 1;
-            int n_keys = n_cache + (is_block ? n_block : 0);
+            /* block keys: all of the block, or (causal variant) the block rows up to this one */
+            int n_keys = n_cache + (is_block ? (c->block_causal ? r - p + 1 : n_block) : 0);
             double *sc = malloc(sizeof(double) * (size_t)n_keys);
             for (int hq = 0; hq < Hq; ++hq) {
                 int hk = hq / G;

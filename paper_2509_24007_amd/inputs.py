@@ -120,6 +120,7 @@ class ModelCfg:
     dtype: str = "bf16"            # "fp32" (debug / tiny) or "bf16"
     has_qkv_bias: bool = True
     mask_token_id: int = -1        # -1 -> vocab - 1
+    block_causal: bool = False     # the "Causal Attention" ablation: causal instead of mutual attention inside the block
 
     def __post_init__(self):
         if self.mask_token_id < 0:
