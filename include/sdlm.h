@@ -61,6 +61,8 @@ typedef struct {
                               bf16 matrix-core inputs, fp32 accumulation, fp32 residual stream and softmax */
     int32_t mask_token_id; /* the id of [m]; its embedding is an ordinary row of the table */
     int32_t has_qkv_bias;
+    int32_t block_causal;  /* 0: full mutual attention inside the block (the method, Sec. 3.3); 1: the ablation of
+                              Sec. 4.4 "Causal Attention": block row k sees the block rows up to itself only */
 } sdlm_model_cfg;
 
 typedef struct {

@@ -101,9 +101,9 @@ struct GemmArgs {
 };
 
 void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows,
-                            int staging_base);
+                            int staging_base, int causal);
 void launch_assemble_verify(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows,
-                            int staging_base);
+                            int staging_base, int causal);
 void launch_verify_accept(hipStream_t s, const SeqState &st, const int32_t *ids_rows, int B, int D, int rule,
                           int32_t *ids_out, int32_t *count_out);
 void launch_embed(hipStream_t s, int dtype, float *x, const void *E, const RowMeta &rm, int max_rows, int h, int V);

@@ -10,7 +10,7 @@ namespace sdlm {
 // Rows of a decode step, per sequence: the pending tokens (positions c..n-1, causal), then the block
 // [x_last, [m] x (D-1)] at positions n-1 .. n+D-2 (block definition, Sec. 3.2).  A block row may see the cache
 // below position s = n-1 only; the causal copy of x_last at s is for later steps.
-__global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mask_id, int gr, int stg0)
+__global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mask_id, int gr, int stg0, int causal)
 {
     __shared__ int row0[1025], grp0[1025];
     if (threadIdx.x == 0) {
@@ -35,7 +35,7 @@ __global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mas
         for (int j = 0; j < D; ++j, ++r) {
             rm.tok[r] = j == 0 ? st.last_tok[b] : mask_id;
             rm.pos[r] = n - 1 + j; rm.seq[r] = b; rm.kind[r] = j; rm.lim[r] = n - 1;
-            rm.stg[r] = stg0 + b; rm.slim[r] = D;
+            rm.stg[r] = stg0 + b; rm.slim[r] = causal ? j + 1 : D;   // block keys: all D, or (causal variant) up to the row itself
             rm.blk_row[b * D + j] = r;
         }
         int rows = p + D, g = grp0[b];
@@ -48,9 +48,10 @@ __global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mas
     }
 }
 
-void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows, int staging_base)
+void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows, int staging_base,
+                            int causal)
 {
-    hipLaunchKernelGGL(assemble_decode_k, dim3(1), dim3(256), 0, s, st, rm, B, D, mask_id, group_rows, staging_base);
+    hipLaunchKernelGGL(assemble_decode_k, dim3(1), dim3(256), 0, s, st, rm, B, D, mask_id, group_rows, staging_base, causal);
 }
 
 // Rows of the verification pass of a self-speculative step (Sec. 3.4, "Self-Speculative Decoding").  With yhat^1..yhat^D
@@ -62,7 +63,7 @@ void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm
 // there) and keep their own K/V in the input's staging tile: a causal row in slot i sees slots [0, i]; a block row
 // sees all j-2+D slots.  Nothing is written to the cache.  Only the first block row of each input goes through the
 // LM head: its arg-max is ytilde^j.
-__global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mask_id, int gr, int stg0)
+__global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mask_id, int gr, int stg0, int causal)
 {
     __shared__ int row0[1025], grp0[1025];
     const int rows_seq = (D - 1) * D + (D - 2) * (D - 1) / 2;
@@ -87,7 +88,7 @@ __global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mas
             }
             for (int t = 0; t < D; ++t, ++r) {
                 rm.tok[r] = t == 0 ? yhat[j - 2] : mask_id; rm.pos[r] = n + j - 2 + t; rm.seq[r] = b; rm.kind[r] = j - 2 + t;
-                rm.lim[r] = n; rm.stg[r] = tile; rm.slim[r] = ns;
+                rm.lim[r] = n; rm.stg[r] = tile; rm.slim[r] = causal ? j - 2 + t + 1 : ns;
                 if (t == 0) rm.blk_row[b * (D - 1) + (j - 2)] = r;
             }
             for (int o = 0; o < ns; o += gr, ++g) {
@@ -101,9 +102,9 @@ __global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mas
 }
 
 void launch_assemble_verify(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows,
-                            int staging_base)
+                            int staging_base, int causal)
 {
-    hipLaunchKernelGGL(assemble_verify_k, dim3(1), dim3(256), 0, s, st, rm, B, D, mask_id, group_rows, staging_base);
+    hipLaunchKernelGGL(assemble_verify_k, dim3(1), dim3(256), 0, s, st, rm, B, D, mask_id, group_rows, staging_base, causal);
 }
 
 // gamma_verify (Eq. 10) from the step's tokens yhat and the verification predictions (ids_rows: ytilde^2..ytilde^D per

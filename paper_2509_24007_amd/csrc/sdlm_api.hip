@@ -45,6 +45,7 @@ bool validate(const sdlm_model_cfg *m, const sdlm_run_cfg *r, std::string *why)
     if (m->head_dim != 32 && m->head_dim != 64 && m->head_dim != 96 && m->head_dim != 128) return bad("head_dim must be 32, 64, 96 or 128");
     if (m->dtype != 0 && m->dtype != 1) return bad("dtype must be 0 (fp32) or 1 (bf16)");
     if (m->mask_token_id < 0 || m->mask_token_id >= m->vocab) return bad("mask_token_id outside the vocabulary");
+    if (m->block_causal != 0 && m->block_causal != 1) return bad("block_causal must be 0 or 1");
     if (r->max_batch < 1 || r->max_batch > 1024) return bad("max_batch must be 1..1024");
     if (r->block_D < 1 || r->block_D > MAX_D) return bad("block_D must be 1..16");
     if (r->page_size != PAGE) return bad("page_size must be 16");
@@ -555,7 +556,7 @@ int sdlm_decode_step(sdlm_ctx *c, int32_t *ids, int32_t *count, float *conf, flo
     }
     hipStream_t s = c->stream;
     const int rows = B * 2 * D;
-    { Phase p(c, SDLM_PH_ROWS); launch_assemble_decode(s, c->st, c->rm, B, D, c->m.mask_token_id, c->L.group_rows, c->kg.staging_base); }
+    { Phase p(c, SDLM_PH_ROWS); launch_assemble_decode(s, c->st, c->rm, B, D, c->m.mask_token_id, c->L.group_rows, c->kg.staging_base, c->m.block_causal); }
     run_layers(c, rows, B * ((2 * D + c->L.group_rows - 1) / c->L.group_rows));
     run_lm_head(c, B * D, logits);
     { Phase p(c, SDLM_PH_ACCEPT); launch_accept(s, c->st, c->ids_rows, c->conf_rows, B, D, c->r.tau, c->r.accept_rule, ids, count, conf); }
@@ -579,7 +580,7 @@ int sdlm_verify_step(sdlm_ctx *c, int32_t rule, int32_t *ids_tilde, int32_t *cou
         const int gr = c->L.group_rows;
         int groups = 0;
         for (int j = 2; j <= D; ++j) groups += (j - 2 + D + gr - 1) / gr;
-        { Phase p(c, SDLM_PH_ROWS); launch_assemble_verify(s, c->st, c->rm, B, D, c->m.mask_token_id, gr, c->kg.staging_base); }
+        { Phase p(c, SDLM_PH_ROWS); launch_assemble_verify(s, c->st, c->rm, B, D, c->m.mask_token_id, gr, c->kg.staging_base, c->m.block_causal); }
         run_layers(c, rows, B * groups);
         run_lm_head(c, B * (D - 1), logits);
     }

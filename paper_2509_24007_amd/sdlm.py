@@ -28,7 +28,8 @@ class ModelCfg(C.Structure):
     _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("ffn", C.c_int32), ("vocab", C.c_int32),
                 ("rope_theta", C.c_float), ("rms_eps", C.c_float), ("logit_scale", C.c_float),
-                ("dtype", C.c_int32), ("mask_token_id", C.c_int32), ("has_qkv_bias", C.c_int32)]
+                ("dtype", C.c_int32), ("mask_token_id", C.c_int32), ("has_qkv_bias", C.c_int32),
+                ("block_causal", C.c_int32)]
 
 
 class RunCfg(C.Structure):
@@ -107,7 +108,7 @@ def model_cfg(m) -> ModelCfg:
     """From the synthetic-input module's ModelCfg (or any object with the same attributes)."""
     return ModelCfg(m.n_layers, m.hidden, m.n_q_heads, m.n_kv_heads, m.head_dim, m.ffn, m.vocab,
                     m.rope_theta, m.rms_eps, m.logit_scale, 0 if m.dtype == "fp32" else 1, m.mask_token_id,
-                    int(bool(m.has_qkv_bias)))
+                    int(bool(m.has_qkv_bias)), int(bool(getattr(m, "block_causal", False))))
 
 
 def _dp(t: Optional[torch.Tensor]):

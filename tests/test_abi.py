@@ -30,5 +30,5 @@ def test_workspace_size_and_validation_without_gpu():
     bad_m = sdlm.ModelCfg(2, 256, 4, 3, 64, 688, 4096, 1e4, 1e-6, 8.0, 0, 4095, 0)
     assert L.sdlm_workspace_bytes(ctypes.byref(bad_m), ctypes.byref(r)) == 0
     # struct layouts agree with the header (field counts and sizes)
-    assert ctypes.sizeof(sdlm.ModelCfg) == 13 * 4 and ctypes.sizeof(sdlm.RunCfg) == 10 * 4
+    assert ctypes.sizeof(sdlm.ModelCfg) == 14 * 4 and ctypes.sizeof(sdlm.RunCfg) == 10 * 4
     assert ctypes.sizeof(sdlm.Weights) == 15 * ctypes.sizeof(ctypes.c_void_p)

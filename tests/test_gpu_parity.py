@@ -357,3 +357,40 @@ def test_verify_bf16_mfma(name, kw, lens, D):
     print(name, st, "verify rows", st.verify_rows, "skipped", st.verify_skipped, "near ties", st.verify_near_tie)
     assert st.verify_rows > 0
     ctx.close()
+
+
+# ------------------------------------------------------------------ causal attention inside the block (Sec. 4.4 ablation)
+@pytest.mark.parametrize("D,paged,verify", [(4, False, None), (8, True, None), (4, True, 0)])
+def test_block_causal_small_fp32(D, paged, verify):
+    m = gpu_cfg(block_causal=True)
+    om, g_dev, layers_dev = both_models(m, seed=7, std=0.3)
+    assert om.cfg.block_causal == 1
+    lens = [1, 5, 16, 31]
+    prompts = [syn.uniform_int(D, f"bc{i}", n, 0, m.vocab - 1).numpy() for i, n in enumerate(lens)]
+    steps = 5
+    ovr = syn.make_overrides(11, steps, len(lens), D, m.vocab)
+    max_len = max(lens) + steps * D + D
+    n_pages = sum((n + steps * D + 15) // 16 + 1 for n in lens)
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=len(lens), max_seq_len=max_len, D=D, tau=0.6, paged=paged, n_pages=n_pages,
+                      prefill_rows=64)
+    st, _ = lockstep(ctx, om, prompts, D, 0.6, steps, logit_tol=1e-4, conf_tol=1e-5, overrides=ovr, max_len=max_len,
+                     verify_rule=verify)
+    print(f"block-causal D={D}", st)
+    assert st.id_near_tie == 0
+    ctx.close()
+
+
+def test_block_causal_bf16_mfma():
+    m = mfma_cfg(block_causal=True)
+    om, g_dev, layers_dev = both_models(m, seed=21, std=0.05)
+    lens = [1, 9, 40, 100]
+    prompts = [syn.uniform_int(4, f"bcm{i}", n, 0, m.vocab - 1).numpy() for i, n in enumerate(lens)]
+    steps = 4
+    max_len = max(lens) + steps * 4 + 4
+    n_pages = sum((n + steps * 4 + 15) // 16 + 1 for n in lens)
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=len(lens), max_seq_len=max_len, D=4, tau=0.6, paged=True, n_pages=n_pages,
+                      prefill_rows=128)
+    assert ctx.kernel_info == "mfma-bf16"
+    st, _ = lockstep(ctx, om, prompts, 4, 0.6, steps, logit_tol=2e-2, conf_tol=1e-3, bf16=True, max_len=max_len, verify_rule=0)
+    print("block-causal mfma", st)
+    ctx.close()
