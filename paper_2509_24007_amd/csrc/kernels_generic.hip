@@ -167,43 +167,68 @@ __device__ inline float block_sum(float v, float *red)
 // out[j,:] = x[row,:] * g / sqrt(mean(x[row,:]^2) + eps), row = row_index ? row_index[j] : j.  When the projection
 // that produced the residual update was split along k, its partial sums (n_slabs slabs of [rows, h]) are first added
 // to x[row,:] in slab order and written back, so the residual stream is complete after this kernel.
-template <typename T>
+// A row lives in registers between the two passes (NV float4 per thread, h <= 1024 NV).
+template <typename T, int NV>
 __global__ __launch_bounds__(256) void rmsnorm_k(T *out, float *x, const T *g, int h, float eps, const int32_t *row_index,
                                                  const int32_t *p_count, const float *slabs, int n_slabs, size_t slab_stride)
 {
     __shared__ float red[4];
-    int j = blockIdx.x;
+    const int j = blockIdx.x;
     if (j >= *p_count) return;
     const int row = row_index ? row_index[j] : j;
     float *xr = x + (size_t)row * h;
-    float ss = 0.f;
-    for (int k = threadIdx.x * 4; k < h; k += 1024) {
-        float4 v = *(const float4 *)(xr + k);
-        if (n_slabs > 0) {
+    float4 v[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int k = (i * 256 + threadIdx.x) * 4;
+        v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (k < h) {
+            v[i] = *(const float4 *)(xr + k);
             for (int sl = 0; sl < n_slabs; ++sl) {
                 float4 p = *(const float4 *)(slabs + sl * slab_stride + (size_t)row * h + k);
-                v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+                v[i].x += p.x; v[i].y += p.y; v[i].z += p.z; v[i].w += p.w;
             }
-            *(float4 *)(xr + k) = v;
         }
-        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    }
+    float ss = 0.f;
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+        const int k = (i * 256 + threadIdx.x) * 4;
+        if (k < h && n_slabs > 0) *(float4 *)(xr + k) = v[i];
+        ss += v[i].x * v[i].x + v[i].y * v[i].y + v[i].z * v[i].z + v[i].w * v[i].w;
     }
     ss = block_sum(ss, red);
-    float inv = 1.0f / sqrtf(ss / (float)h + eps);
-    for (int k = threadIdx.x * 4; k < h; k += 1024) {
-        float4 v = *(const float4 *)(xr + k);   // this thread's own elements: written above by itself
-        T o[4] = {from_f<T>(v.x * inv * to_f<T>(g[k])), from_f<T>(v.y * inv * to_f<T>(g[k + 1])),
-                  from_f<T>(v.z * inv * to_f<T>(g[k + 2])), from_f<T>(v.w * inv * to_f<T>(g[k + 3]))};
+    const float inv = 1.0f / sqrtf(ss / (float)h + eps);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) out[(size_t)j * h + k + e] = o[e];
+    for (int i = 0; i < NV; ++i) {
+        const int k = (i * 256 + threadIdx.x) * 4;
+        if (k >= h) continue;
+        const float o0 = v[i].x * inv * to_f<T>(g[k]), o1 = v[i].y * inv * to_f<T>(g[k + 1]);
+        const float o2 = v[i].z * inv * to_f<T>(g[k + 2]), o3 = v[i].w * inv * to_f<T>(g[k + 3]);
+        T *dst = out + (size_t)j * h + k;
+        if constexpr (sizeof(T) == 2) {
+            *(uint2 *)dst = make_uint2((uint32_t)f_to_bf16(o0) | ((uint32_t)f_to_bf16(o1) << 16),
+                                       (uint32_t)f_to_bf16(o2) | ((uint32_t)f_to_bf16(o3) << 16));
+        } else {
+            *(float4 *)dst = make_float4(o0, o1, o2, o3);
+        }
     }
+}
+
+template <typename T>
+static void rmsnorm_t(hipStream_t s, void *out, float *x, const void *g, int h, float eps, const int32_t *row_index,
+                      const int32_t *p_count, int max_rows, const float *slabs, int n_slabs, size_t slab_stride)
+{
+#define SDLM_RMS(NV) hipLaunchKernelGGL((rmsnorm_k<T, NV>), dim3(max_rows), dim3(256), 0, s, (T *)out, x, (const T *)g, h, eps, row_index, p_count, slabs, n_slabs, slab_stride)
+    if (h <= 2048) SDLM_RMS(2); else if (h <= 4096) SDLM_RMS(4); else if (h <= 8192) SDLM_RMS(8); else SDLM_RMS(16);
+#undef SDLM_RMS
 }
 
 void launch_rmsnorm(hipStream_t s, int dtype, void *out, float *x, const void *g, int h, float eps, const int32_t *row_index,
                     const int32_t *p_count, int max_rows, const float *slabs, int n_slabs, size_t slab_stride)
 {
-    if (dtype == 0) hipLaunchKernelGGL(rmsnorm_k<float>, dim3(max_rows), dim3(256), 0, s, (float *)out, x, (const float *)g, h, eps, row_index, p_count, slabs, n_slabs, slab_stride);
-    else hipLaunchKernelGGL(rmsnorm_k<bf16_t>, dim3(max_rows), dim3(256), 0, s, (bf16_t *)out, x, (const bf16_t *)g, h, eps, row_index, p_count, slabs, n_slabs, slab_stride);
+    if (dtype == 0) rmsnorm_t<float>(s, out, x, g, h, eps, row_index, p_count, max_rows, slabs, n_slabs, slab_stride);
+    else rmsnorm_t<bf16_t>(s, out, x, g, h, eps, row_index, p_count, max_rows, slabs, n_slabs, slab_stride);
 }
 
 // ------------------------------------------------------------------------------------------------ GEMM (FMA)
@@ -283,51 +308,50 @@ void launch_gemm_generic(hipStream_t s, int dtype, int epi, const GemmArgs &a)
 // qkv: raw projections [R, (Hq + 2 Hkv) d] fp32, given as n_slabs partial sums that are added in order.  Queries and keys are rotated at the row's position (rotate-half
 // pairing i <-> i + d/2).  A pending row's K/V go to the cache slot of its position: they are final.  A block
 // row's K/V (and, in a verification pass, every row's) go to slot `kind` of the row's staging tile: they are never cached.
+// grid (rows, ceil((Hq + 2 Hkv) / 4)): one wavefront per (row, head), lane i < d/2 owns the pair (i, i + d/2).
 template <typename T>
 __global__ __launch_bounds__(256) void rope_scatter_k(const float *qkv, int n_slabs, size_t slab_stride, T *q_out, T *pool, KvGeom kg,
                                                       RowMeta rm, SeqState st, const float2 *rope, int Hq)
 {
-    int r = blockIdx.x;
-    if (r >= rm.counts[0]) return;
+    const int r = blockIdx.x;
     const int d = kg.head_dim, half = d >> 1, Hk = kg.n_kv_heads, nq = Hq * d, nk = Hk * d;
-    const float *row = qkv + (size_t)r * (nq + 2 * nk);
-    auto val = [&](int col) {
-        float v = row[col];
-        for (int sl = 1; sl < n_slabs; ++sl) v += row[sl * slab_stride + col];
-        return v;
-    };
-    const int pos = rm.pos[r], kind = rm.kind[r], b = rm.seq[r];
-    const float2 *cs = rope + (size_t)pos * half;
+    const int head = blockIdx.y * 4 + (threadIdx.x >> 6), i = threadIdx.x & 63;   // heads: Hq of q, then Hkv of k, then Hkv of v
+    if (head >= Hq + 2 * Hk || i >= half || r >= rm.counts[0]) return;
+    const float *src = qkv + (size_t)r * (nq + 2 * nk) + head * d + i;
+    float x0 = src[0], x1 = src[half];
+    for (int sl = 1; sl < n_slabs; ++sl) { x0 += src[sl * slab_stride]; x1 += src[sl * slab_stride + half]; }
+    const int pos = rm.pos[r], kind = rm.kind[r], b = rm.seq[r], stg = rm.stg[r];
+    if (head < Hq) {
+        const float2 t = rope[(size_t)pos * half + i];
+        T *q = q_out + (size_t)r * nq + head * d + i;
+        q[0] = from_f<T>(x0 * t.x - x1 * t.y);
+        q[half] = from_f<T>(x1 * t.x + x0 * t.y);
+        return;
+    }
     int page, slot;
     if (kind < 0) { page = st.page_table[(size_t)b * kg.pages_per_seq + pos / PAGE]; slot = pos % PAGE; }
-    else { page = rm.stg[r]; slot = kind; }
-    for (int e = threadIdx.x; e < Hq * half; e += 256) {
-        int hq = e / half, i = e % half;
-        float2 t = cs[i];
-        float x0 = val(hq * d + i), x1 = val(hq * d + i + half);
-        q_out[(size_t)r * nq + hq * d + i] = from_f<T>(x0 * t.x - x1 * t.y);
-        q_out[(size_t)r * nq + hq * d + i + half] = from_f<T>(x1 * t.x + x0 * t.y);
-    }
+    else { page = stg; slot = kind; }
     if (page < 0) return;   // unbacked position: only reachable after a reported pool exhaustion
-    for (int e = threadIdx.x; e < Hk * half; e += 256) {
-        int hk = e / half, i = e % half;
-        float2 t = cs[i];
-        const int kc = nq + hk * d, vc = nq + nk + hk * d;
-        T *tile = pool + kg.tile(page, hk);
-        T *Kb = tile, *Vb = tile + PAGE * d;
-        float x0 = val(kc + i), x1 = val(kc + i + half);
-        Kb[k_off(slot, i)] = from_f<T>(x0 * t.x - x1 * t.y);
-        Kb[k_off(slot, i + half)] = from_f<T>(x1 * t.x + x0 * t.y);
-        Vb[v_off(slot, i)] = from_f<T>(val(vc + i));
-        Vb[v_off(slot, i + half)] = from_f<T>(val(vc + i + half));
+    const bool is_k = head < Hq + Hk;
+    const int hk = is_k ? head - Hq : head - Hq - Hk;
+    T *tile = pool + kg.tile(page, hk);
+    if (is_k) {
+        const float2 t = rope[(size_t)pos * half + i];
+        tile[k_off(slot, i)] = from_f<T>(x0 * t.x - x1 * t.y);
+        tile[k_off(slot, i + half)] = from_f<T>(x1 * t.x + x0 * t.y);
+    } else {
+        T *Vb = tile + PAGE * d;
+        Vb[v_off(slot, i)] = from_f<T>(x0);
+        Vb[v_off(slot, i + half)] = from_f<T>(x1);
     }
 }
 
 void launch_rope_scatter(hipStream_t s, int dtype, const float *qkv, int n_slabs, size_t slab_stride, void *q_out, void *pool_layer,
                          const KvGeom &kg, const RowMeta &rm, const SeqState &st, const float2 *rope, int n_q_heads, int max_rows)
 {
-    if (dtype == 0) hipLaunchKernelGGL(rope_scatter_k<float>, dim3(max_rows), dim3(256), 0, s, qkv, n_slabs, slab_stride, (float *)q_out, (float *)pool_layer, kg, rm, st, rope, n_q_heads);
-    else hipLaunchKernelGGL(rope_scatter_k<bf16_t>, dim3(max_rows), dim3(256), 0, s, qkv, n_slabs, slab_stride, (bf16_t *)q_out, (bf16_t *)pool_layer, kg, rm, st, rope, n_q_heads);
+    dim3 grid(max_rows, (n_q_heads + 2 * kg.n_kv_heads + 3) / 4);
+    if (dtype == 0) hipLaunchKernelGGL(rope_scatter_k<float>, grid, dim3(256), 0, s, qkv, n_slabs, slab_stride, (float *)q_out, (float *)pool_layer, kg, rm, st, rope, n_q_heads);
+    else hipLaunchKernelGGL(rope_scatter_k<bf16_t>, grid, dim3(256), 0, s, qkv, n_slabs, slab_stride, (bf16_t *)q_out, (bf16_t *)pool_layer, kg, rm, st, rope, n_q_heads);
 }
 
 // ------------------------------------------------------------------------------------------------ attention

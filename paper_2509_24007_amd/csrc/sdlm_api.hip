@@ -41,6 +41,7 @@ bool validate(const sdlm_model_cfg *m, const sdlm_run_cfg *r, std::string *why)
     auto bad = [&](const char *s) { if (why) *why = s; return false; };
     if (!m || !r) return bad("null configuration");
     if (m->n_layers < 1 || m->hidden < 8 || m->ffn < 8 || m->vocab < 2) return bad("bad model sizes");
+    if (m->hidden % 4 || m->hidden > 16384) return bad("hidden must be a multiple of 4, at most 16384");
     if (m->n_kv_heads < 1 || m->n_q_heads < 1 || m->n_q_heads % m->n_kv_heads) return bad("n_q_heads must be a multiple of n_kv_heads");
     if (m->head_dim != 32 && m->head_dim != 64 && m->head_dim != 96 && m->head_dim != 128) return bad("head_dim must be 32, 64, 96 or 128");
     if (m->dtype != 0 && m->dtype != 1) return bad("dtype must be 0 (fp32) or 1 (bf16)");
