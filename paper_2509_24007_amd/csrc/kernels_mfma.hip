@@ -137,35 +137,27 @@ __global__ __launch_bounds__(256, (w_sets<MT, NT>() == 2 ? 2 : 1)) void gemm_mfm
 #define SDLM_LOAD_X(stage)                                                                                        \
     {                                                                                                             \
         const size_t xo_ = (size_t)min((stage), s_last) * 64;                                                     \
-        _Pragma("unroll") for (int i = 0; i < MT; ++i) xr[i] = *(const u32x4 *)(a.X + xo_ + xoff[i]);                    \
+        _Pragma("unroll") for (int i = 0; i < MTA_; ++i) xr[i] = *(const u32x4 *)(a.X + xo_ + xoff[i]);          \
     }
-    SDLM_LOAD_X(s_begin);
     constexpr int WSETS = w_sets<MT, NT>();
-    SDLM_LOAD_W(w0, s_begin);
-    if (WSETS == 3) SDLM_LOAD_W(w1, s_begin + 1);
-#pragma unroll
-    for (int i = 0; i < MT; ++i) *(u32x4 *)&Xs[0][i * 32 + xrow][xchunk * 8] = xr[i];
-    __syncthreads();
-
     const int brow = lane & 31, bk = (lane >> 5) * 8;
-    int buf = 0;
 /* one k-step: request the LDS operands of the next k-step, run this k-step's MFMAs, and pin that order */
 #define SDLM_KSTEP(WC, ks, has_next)                                                                              \
     {                                                                                                             \
         if (WSETS == 3) {                                                                                         \
             if (has_next) {                                                                                       \
-                _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                                \
+                _Pragma("unroll") for (int mt = 0; mt < MTA_; ++mt)                                              \
                     bn_[mt] = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][((ks) + 1) * 16 + bk];                    \
             }                                                                                                     \
-            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt)                                                    \
+            _Pragma("unroll") for (int mt = 0; mt < MTA_; ++mt)                                                  \
                 _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                \
                     acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WC[nt][ks], bc_[mt], acc[nt][mt], 0, 0, 0); \
-            __builtin_amdgcn_sched_group_barrier(0x100, (has_next) ? MT : 0, 0);                                  \
-            __builtin_amdgcn_sched_group_barrier(0x008, MT * NT, 0);                                              \
-            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) bc_[mt] = bn_[mt];                                 \
+            __builtin_amdgcn_sched_group_barrier(0x100, (has_next) ? MTA_ : 0, 0);                                \
+            __builtin_amdgcn_sched_group_barrier(0x008, MTA_ * NT, 0);                                            \
+            _Pragma("unroll") for (int mt = 0; mt < MTA_; ++mt) bc_[mt] = bn_[mt];                               \
         } else {                                                                                                  \
             /* one operand set: each fragment is re-read in place right after the MFMAs that used it */           \
-            _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) {                                                  \
+            _Pragma("unroll") for (int mt = 0; mt < MTA_; ++mt) {                                                \
                 _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                \
                     acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WC[nt][ks], bc_[mt], acc[nt][mt], 0, 0, 0); \
                 if (has_next) bc_[mt] = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][((ks) + 1) * 16 + bk];          \
@@ -177,37 +169,58 @@ __global__ __launch_bounds__(256, (w_sets<MT, NT>() == 2 ? 2 : 1)) void gemm_mfm
 #define SDLM_STAGE(WC, WN, stage)                                                                                 \
     {                                                                                                             \
         SDLM_LOAD_X((stage) + 1);                                                                                 \
-        SDLM_LOAD_W(WN, (stage) + WSETS - 1);                                                                             \
+        SDLM_LOAD_W(WN, (stage) + WSETS - 1);                                                                     \
         __builtin_amdgcn_sched_barrier(0);                                                                        \
-        bf16x8 bc_[MT], bn_[WSETS == 3 ? MT : 1];                                                                                  \
-        _Pragma("unroll") for (int mt = 0; mt < MT; ++mt) bc_[mt] = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][bk]; \
-        __builtin_amdgcn_sched_group_barrier(0x100, MT, 0);                                                       \
+        bf16x8 bc_[MT], bn_[WSETS == 3 ? MT : 1];                                                                 \
+        _Pragma("unroll") for (int mt = 0; mt < MTA_; ++mt) bc_[mt] = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][bk]; \
+        __builtin_amdgcn_sched_group_barrier(0x100, MTA_, 0);                                                     \
         SDLM_KSTEP(WC, 0, 1) SDLM_KSTEP(WC, 1, 1) SDLM_KSTEP(WC, 2, 1) SDLM_KSTEP(WC, 3, 0)                       \
         __builtin_amdgcn_sched_barrier(0);                                                                        \
-        _Pragma("unroll") for (int i = 0; i < MT; ++i) *(u32x4 *)&Xs[buf ^ 1][i * 32 + xrow][xchunk * 8] = xr[i]; \
+        _Pragma("unroll") for (int i = 0; i < MTA_; ++i) *(u32x4 *)&Xs[buf ^ 1][i * 32 + xrow][xchunk * 8] = xr[i]; \
         buf ^= 1;                                                                                                 \
         __syncthreads();                                                                                          \
     }
-    // Full triples run without any branch inside the loop (a conditional stage would make the compiler drain all
-    // outstanding loads at the loop head); the 0..2 remaining slices are peeled.
-    int s = s_begin;
-    if (WSETS == 3) {
-        for (; s + 3 <= s_end; s += 3) {
-            SDLM_STAGE(w0, w2, s)
-            SDLM_STAGE(w1, w0, s + 1)
-            SDLM_STAGE(w2, w1, s + 2)
-        }
-        if (s < s_end) {
-            SDLM_STAGE(w0, w2, s)
-            if (s + 1 < s_end) SDLM_STAGE(w1, w0, s + 1)
-        }
-    } else {
-        for (; s + 2 <= s_end; s += 2) {
-            SDLM_STAGE(w0, w1, s)
-            SDLM_STAGE(w1, w0, s + 1)
-        }
-        if (s < s_end) SDLM_STAGE(w0, w1, s)
+/* The whole k loop for a row block of which only the first MTA_VALUE 32-row sub-tiles hold rows (the last block of
+   a launch is usually ragged): the empty sub-tiles' loads, LDS traffic and MFMAs are not issued at all.  Full
+   triples (pairs) of slices run without any branch inside the loop (a conditional stage would make the compiler
+   drain all outstanding loads at the loop head); the remaining slices are peeled. */
+#define SDLM_MAIN(MTA_VALUE)                                                                                      \
+    {                                                                                                             \
+        constexpr int MTA_ = MTA_VALUE;                                                                           \
+        int buf = 0;                                                                                              \
+        SDLM_LOAD_X(s_begin);                                                                                     \
+        SDLM_LOAD_W(w0, s_begin);                                                                                 \
+        if (WSETS == 3) SDLM_LOAD_W(w1, s_begin + 1);                                                             \
+        _Pragma("unroll") for (int i = 0; i < MTA_; ++i) *(u32x4 *)&Xs[0][i * 32 + xrow][xchunk * 8] = xr[i];    \
+        __syncthreads();                                                                                          \
+        int s = s_begin;                                                                                          \
+        if (WSETS == 3) {                                                                                         \
+            for (; s + 3 <= s_end; s += 3) {                                                                      \
+                SDLM_STAGE(w0, w2, s)                                                                             \
+                SDLM_STAGE(w1, w0, s + 1)                                                                         \
+                SDLM_STAGE(w2, w1, s + 2)                                                                         \
+            }                                                                                                     \
+            if (s < s_end) {                                                                                      \
+                SDLM_STAGE(w0, w2, s)                                                                             \
+                if (s + 1 < s_end) SDLM_STAGE(w1, w0, s + 1)                                                      \
+            }                                                                                                     \
+        } else {                                                                                                  \
+            for (; s + 2 <= s_end; s += 2) {                                                                      \
+                SDLM_STAGE(w0, w1, s)                                                                             \
+                SDLM_STAGE(w1, w0, s + 1)                                                                         \
+            }                                                                                                     \
+            if (s < s_end) SDLM_STAGE(w0, w1, s)                                                                  \
+        }                                                                                                         \
     }
+    const int mt_act = min(MT, (R - m0 + 31) >> 5);   // >= 1: m0 < R
+    if constexpr (MT == 4) {
+        if (mt_act == 4) SDLM_MAIN(4) else if (mt_act == 3) SDLM_MAIN(3) else if (mt_act == 2) SDLM_MAIN(2) else SDLM_MAIN(1)
+    } else if constexpr (MT == 2) {
+        if (mt_act == 2) SDLM_MAIN(2) else SDLM_MAIN(1)
+    } else {
+        SDLM_MAIN(1)
+    }
+#undef SDLM_MAIN
 #undef SDLM_STAGE
 #undef SDLM_KSTEP
 #undef SDLM_LOAD_W
