@@ -131,8 +131,9 @@ __global__ __launch_bounds__(256, (w_sets<MT, NT>() == 2 ? 2 : 1)) void gemm_mfm
 #define SDLM_LOAD_W(dst, stage)                                                                                   \
     {                                                                                                             \
         const size_t so_ = (size_t)min((stage), s_last) * 4 * 512;                                                \
-        _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                        \
-            _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) dst[nt][ks] = *(const bf16x8 *)(wp[nt] + so_ + ks * 512 + wlane); \
+        /* in the order the next slice's k-steps consume them */                                                  \
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                                         \
+            _Pragma("unroll") for (int nt = 0; nt < NT; ++nt) dst[nt][ks] = *(const bf16x8 *)(wp[nt] + so_ + ks * 512 + wlane); \
     }
 #define SDLM_LOAD_X(stage)                                                                                        \
     {                                                                                                             \
@@ -141,40 +142,59 @@ __global__ __launch_bounds__(256, (w_sets<MT, NT>() == 2 ? 2 : 1)) void gemm_mfm
     }
     constexpr int WSETS = w_sets<MT, NT>();
     const int brow = lane & 31, bk = (lane >> 5) * 8;
-/* one k-step: request the LDS operands of the next k-step, run this k-step's MFMAs, and pin that order */
+/* ---- three weight sets (small tiles): one k-step = request the LDS operands of the next k-step, run this k-step's
+   MFMAs, and pin that order; the slice's global loads are issued at its top */
 #define SDLM_KSTEP(WC, ks, has_next)                                                                              \
     {                                                                                                             \
-        if (WSETS == 3) {                                                                                         \
-            if (has_next) {                                                                                       \
-                _Pragma("unroll") for (int mt = 0; mt < MTA_; ++mt)                                              \
-                    bn_[mt] = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][((ks) + 1) * 16 + bk];                    \
-            }                                                                                                     \
+        if (has_next) {                                                                                           \
             _Pragma("unroll") for (int mt = 0; mt < MTA_; ++mt)                                                  \
-                _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                \
-                    acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WC[nt][ks], bc_[mt], acc[nt][mt], 0, 0, 0); \
-            __builtin_amdgcn_sched_group_barrier(0x100, (has_next) ? MTA_ : 0, 0);                                \
-            __builtin_amdgcn_sched_group_barrier(0x008, MTA_ * NT, 0);                                            \
-            _Pragma("unroll") for (int mt = 0; mt < MTA_; ++mt) bc_[mt] = bn_[mt];                               \
-        } else {                                                                                                  \
-            /* one operand set: each fragment is re-read in place right after the MFMAs that used it */           \
-            _Pragma("unroll") for (int mt = 0; mt < MTA_; ++mt) {                                                \
-                _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                \
-                    acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WC[nt][ks], bc_[mt], acc[nt][mt], 0, 0, 0); \
-                if (has_next) bc_[mt] = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][((ks) + 1) * 16 + bk];          \
-                __builtin_amdgcn_sched_group_barrier(0x008, NT, 0);                                               \
-                __builtin_amdgcn_sched_group_barrier(0x100, (has_next) ? 1 : 0, 0);                               \
-            }                                                                                                     \
+                bn_[mt] = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][((ks) + 1) * 16 + bk];                        \
         }                                                                                                         \
+        _Pragma("unroll") for (int mt = 0; mt < MTA_; ++mt)                                                      \
+            _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                    \
+                acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WC[nt][ks], bc_[mt], acc[nt][mt], 0, 0, 0); \
+        __builtin_amdgcn_sched_group_barrier(0x100, (has_next) ? MTA_ : 0, 0);                                    \
+        __builtin_amdgcn_sched_group_barrier(0x008, MTA_ * NT, 0);                                                \
+        _Pragma("unroll") for (int mt = 0; mt < MTA_; ++mt) bc_[mt] = bn_[mt];                                   \
     }
-#define SDLM_STAGE(WC, WN, stage)                                                                                 \
+#define SDLM_STAGE3(WC, WN, stage)                                                                                \
     {                                                                                                             \
         SDLM_LOAD_X((stage) + 1);                                                                                 \
-        SDLM_LOAD_W(WN, (stage) + WSETS - 1);                                                                     \
+        SDLM_LOAD_W(WN, (stage) + 2);                                                                             \
         __builtin_amdgcn_sched_barrier(0);                                                                        \
-        bf16x8 bc_[MT], bn_[WSETS == 3 ? MT : 1];                                                                 \
+        bf16x8 bc_[MT], bn_[MT];                                                                                  \
         _Pragma("unroll") for (int mt = 0; mt < MTA_; ++mt) bc_[mt] = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][bk]; \
         __builtin_amdgcn_sched_group_barrier(0x100, MTA_, 0);                                                     \
         SDLM_KSTEP(WC, 0, 1) SDLM_KSTEP(WC, 1, 1) SDLM_KSTEP(WC, 2, 1) SDLM_KSTEP(WC, 3, 0)                       \
+        __builtin_amdgcn_sched_barrier(0);                                                                        \
+        _Pragma("unroll") for (int i = 0; i < MTA_; ++i) *(u32x4 *)&Xs[buf ^ 1][i * 32 + xrow][xchunk * 8] = xr[i]; \
+        buf ^= 1;                                                                                                 \
+        __syncthreads();                                                                                          \
+    }
+/* ---- two weight sets (128-row tiles): a single activation operand set bq_; each fragment is re-read in place
+   right after the MFMAs that used it (slot = the MFMAs of one 32-row sub-tile at one k-step).  The slice's global
+   loads are dealt out one per slot so that the load unit never holds the wavefront up: activations first, then
+   weights in the order the next slice consumes them.  (Publishing the next activations before the last k-step, to
+   cover the barrier with MFMAs, was measured and is slower: it shortens the time the activation loads have to land.) */
+#define SDLM_SLOT(WC, ks, mt, reload)                                                                             \
+    if constexpr ((mt) < MTA_) {                                                                                  \
+        _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                        \
+            acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WC[nt][ks], bq_[mt], acc[nt][mt], 0, 0, 0);     \
+        if (reload) bq_[mt] = *(const bf16x8 *)&Xs[buf][(mt) * 32 + brow][((ks) + 1) * 16 + bk];                  \
+        __builtin_amdgcn_sched_group_barrier(0x020, ((ks) * MTA_ + (mt) < MTA_ + 4 * NT) ? 1 : 0, 0);             \
+        __builtin_amdgcn_sched_group_barrier(0x008, NT, 0);                                                       \
+        __builtin_amdgcn_sched_group_barrier(0x100, (reload) ? 1 : 0, 0);                                         \
+    }
+#define SDLM_KSTEP2(WC, ks, reload)                                                                               \
+    SDLM_SLOT(WC, ks, 0, reload) SDLM_SLOT(WC, ks, 1, reload) SDLM_SLOT(WC, ks, 2, reload) SDLM_SLOT(WC, ks, 3, reload)
+#define SDLM_STAGE2(WC, WN, stage)                                                                                \
+    {                                                                                                             \
+        SDLM_LOAD_X((stage) + 1);                                                                                 \
+        SDLM_LOAD_W(WN, (stage) + 1);                                                                             \
+        bf16x8 bq_[MT];                                                                                           \
+        _Pragma("unroll") for (int mt = 0; mt < MTA_; ++mt) bq_[mt] = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][bk]; \
+        __builtin_amdgcn_sched_group_barrier(0x100, MTA_, 0);                                                     \
+        SDLM_KSTEP2(WC, 0, 1) SDLM_KSTEP2(WC, 1, 1) SDLM_KSTEP2(WC, 2, 1) SDLM_KSTEP2(WC, 3, 0)                   \
         __builtin_amdgcn_sched_barrier(0);                                                                        \
         _Pragma("unroll") for (int i = 0; i < MTA_; ++i) *(u32x4 *)&Xs[buf ^ 1][i * 32 + xrow][xchunk * 8] = xr[i]; \
         buf ^= 1;                                                                                                 \
@@ -194,22 +214,22 @@ __global__ __launch_bounds__(256, (w_sets<MT, NT>() == 2 ? 2 : 1)) void gemm_mfm
         _Pragma("unroll") for (int i = 0; i < MTA_; ++i) *(u32x4 *)&Xs[0][i * 32 + xrow][xchunk * 8] = xr[i];    \
         __syncthreads();                                                                                          \
         int s = s_begin;                                                                                          \
-        if (WSETS == 3) {                                                                                         \
+        if constexpr (WSETS == 3) {                                                                               \
             for (; s + 3 <= s_end; s += 3) {                                                                      \
-                SDLM_STAGE(w0, w2, s)                                                                             \
-                SDLM_STAGE(w1, w0, s + 1)                                                                         \
-                SDLM_STAGE(w2, w1, s + 2)                                                                         \
+                SDLM_STAGE3(w0, w2, s)                                                                            \
+                SDLM_STAGE3(w1, w0, s + 1)                                                                        \
+                SDLM_STAGE3(w2, w1, s + 2)                                                                        \
             }                                                                                                     \
             if (s < s_end) {                                                                                      \
-                SDLM_STAGE(w0, w2, s)                                                                             \
-                if (s + 1 < s_end) SDLM_STAGE(w1, w0, s + 1)                                                      \
+                SDLM_STAGE3(w0, w2, s)                                                                            \
+                if (s + 1 < s_end) SDLM_STAGE3(w1, w0, s + 1)                                                     \
             }                                                                                                     \
         } else {                                                                                                  \
             for (; s + 2 <= s_end; s += 2) {                                                                      \
-                SDLM_STAGE(w0, w1, s)                                                                             \
-                SDLM_STAGE(w1, w0, s + 1)                                                                         \
+                SDLM_STAGE2(w0, w1, s)                                                                            \
+                SDLM_STAGE2(w1, w0, s + 1)                                                                        \
             }                                                                                                     \
-            if (s < s_end) SDLM_STAGE(w0, w1, s)                                                                  \
+            if (s < s_end) SDLM_STAGE2(w0, w1, s)                                                                 \
         }                                                                                                         \
     }
     const int mt_act = min(MT, (R - m0 + 31) >> 5);   // >= 1: m0 < R
@@ -221,8 +241,11 @@ __global__ __launch_bounds__(256, (w_sets<MT, NT>() == 2 ? 2 : 1)) void gemm_mfm
         SDLM_MAIN(1)
     }
 #undef SDLM_MAIN
-#undef SDLM_STAGE
+#undef SDLM_STAGE3
+#undef SDLM_STAGE2
 #undef SDLM_KSTEP
+#undef SDLM_KSTEP2
+#undef SDLM_SLOT
 #undef SDLM_LOAD_W
 #undef SDLM_LOAD_X
 
