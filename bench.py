@@ -50,6 +50,7 @@ def parse():
                     help="phases bracketed by HIP events inside the timed region: one phase name (default: the dominant kernel), "
                          "main (all six big kernels, ~6%% slower steps) or none; the per-kernel table of the other phases comes "
                          "from up to 32 extra untimed steps")
+    ap.add_argument("--prefill-rows", type=int, default=0, help="rows per prefill pass (0: library default)")
     ap.add_argument("--verify", type=int, default=None, choices=(0, 1),
                     help="self-speculative decoding: every step is followed by the verification pass and commits gamma_verify "
                          "tokens (rule 0: agreeing prefix, 1: largest agreeing index); no per-kernel table in this mode")
@@ -95,8 +96,11 @@ def run_tau(ctx, m, r, prompts, tau_idx, steps, warmup, prof_phases, table_steps
     per launch), then `table_steps` untimed extra steps with every main phase bracketed for the per-kernel table."""
     import torch
     B, D = len(prompts), r.block_D
+    torch.cuda.synchronize()
+    tp = time.perf_counter()
     ctx.prefill(prompts)
     torch.cuda.synchronize()
+    run_tau.prefill_s = time.perf_counter() - tp
     ids = torch.zeros(warmup + steps + table_steps, B, D, dtype=torch.int32, device="cuda")
     cnt = torch.zeros(warmup + steps + table_steps, B, dtype=torch.int32, device="cuda")
     def one(t):
@@ -179,7 +183,7 @@ def main():
     max_len = max(len(p) for p in prompts) + total_steps * D + D
     n_pages = sum((len(p) + total_steps * D + D + 15) // 16 + 1 for p in prompts) if r.paged else 0
     ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=B, max_seq_len=max_len, block_D=D, tau=tau, paged=r.paged,
-                       n_pages=n_pages)
+                       n_pages=n_pages, prefill_rows=a.prefill_rows)
     want_cpu = not a.no_cpu_baseline
     t0 = time.perf_counter()
     host_g, host_layers = build_model(ctx, m, wl.seed, keep_host_layers=m.n_layers if want_cpu else None)
@@ -192,7 +196,8 @@ def main():
     for ti, tv in enumerate(taus):
         if ti > 0:
             ctx.close()
-            ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=B, max_seq_len=max_len, block_D=D, tau=tv, paged=r.paged, n_pages=n_pages)
+            ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=B, max_seq_len=max_len, block_D=D, tau=tv, paged=r.paged, n_pages=n_pages,
+                               prefill_rows=a.prefill_rows)
             build_model(ctx, m, wl.seed)
         t0 = time.perf_counter()
         dt, cnt, phases, n_end, tphases = run_tau(ctx, m, r, prompts, ti, a.steps, a.warmup, prof, table_steps if ti == 0 else 0, a.verify)
@@ -277,6 +282,10 @@ def main():
         "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
         "roofline": roof,
         "kernels": {k: {kk: (round(vv, 3) if isinstance(vv, float) else vv) for kk, vv in v.items()} for k, v in table.items()},
+        "prefill": {"prompt_tokens": int(sum(len(p) for p in prompts)), "seconds": round(run_tau.prefill_s, 3),
+                    "tokens_per_s": sum(len(p) for p in prompts) / run_tau.prefill_s,
+                    "note": "causal pass over the prompts through the same kernels (pending-row path), LM head skipped; "
+                            "prompts come from host memory; last tau's run when sweeping"},
         "setup_s": {"weights": round(t_build, 1), "prefill_and_run": round(main_r["t_total"], 1)},
     }
     if a.verify is not None:    # the byte accounting above describes the block step alone
