@@ -55,8 +55,6 @@ def parse():
                     help="self-speculative decoding: every step is followed by the verification pass and commits gamma_verify "
                          "tokens (rule 0: agreeing prefix, 1: largest agreeing index); no per-kernel table in this mode")
     ap.add_argument("--profile-all", action="store_true", help="bracket every phase with events (adds overhead)")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="run one plain 1 GiB device copy first: under rocprofv3 --pmc its FETCH_SIZE / WRITE_SIZE give the counter scale")
     return ap.parse_args()
 
 
@@ -157,21 +155,13 @@ def main():
     a = parse()
     if a.gpus != 1:
         print("bench.py: this build measures the block-decode step on ONE GPU; --gpus %d is not supported "
-              "(the path shards by sequences, see DESIGN.md)" % a.gpus, file=sys.stderr)
+              "(sequences are independent: more GPUs would each take a share of the batch)" % a.gpus, file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch
     from paper_2509_24007_amd import inputs as syn
     from paper_2509_24007_amd import sdlm
 
-    if a.calibrate_copy:
-        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB read, 1 GiB written
-        dst = torch.empty_like(src)
-        torch.cuda.synchronize()
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-        torch.cuda.empty_cache()
     wl = syn.workloads()[a.config]
     m, r = wl.model, wl.run
     tau = a.tau if a.tau is not None else r.tau
