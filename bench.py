@@ -54,6 +54,9 @@ def parse():
     ap.add_argument("--verify", type=int, default=None, choices=(0, 1),
                     help="self-speculative decoding: every step is followed by the verification pass and commits gamma_verify "
                          "tokens (rule 0: agreeing prefix, 1: largest agreeing index); no per-kernel table in this mode")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay the decode step as a HIP graph (library on a side stream); steps run eagerly while any phase "
+                         "carries events, so combine with --phases none")
     ap.add_argument("--profile-all", action="store_true", help="bracket every phase with events (adds overhead)")
     return ap.parse_args()
 
@@ -172,8 +175,13 @@ def main():
     total_steps = a.warmup + a.steps + table_steps
     max_len = max(len(p) for p in prompts) + total_steps * D + D
     n_pages = sum((len(p) + total_steps * D + D + 15) // 16 + 1 for p in prompts) if r.paged else 0
-    ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=B, max_seq_len=max_len, block_D=D, tau=tau, paged=r.paged,
-                       n_pages=n_pages, prefill_rows=a.prefill_rows)
+    side = torch.cuda.Stream() if a.graph else None
+    with torch.cuda.stream(side):
+        ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=B, max_seq_len=max_len, block_D=D, tau=tau, paged=r.paged,
+                           n_pages=n_pages, prefill_rows=a.prefill_rows)
+    torch.cuda.synchronize()
+    if a.graph:
+        ctx.graph(True)
     want_cpu = not a.no_cpu_baseline
     t0 = time.perf_counter()
     host_g, host_layers = build_model(ctx, m, wl.seed, keep_host_layers=m.n_layers if want_cpu else None)
@@ -186,8 +194,12 @@ def main():
     for ti, tv in enumerate(taus):
         if ti > 0:
             ctx.close()
-            ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=B, max_seq_len=max_len, block_D=D, tau=tv, paged=r.paged, n_pages=n_pages,
-                               prefill_rows=a.prefill_rows)
+            with torch.cuda.stream(side):
+                ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=B, max_seq_len=max_len, block_D=D, tau=tv, paged=r.paged, n_pages=n_pages,
+                                   prefill_rows=a.prefill_rows)
+            torch.cuda.synchronize()
+            if a.graph:
+                ctx.graph(True)
             build_model(ctx, m, wl.seed)
         t0 = time.perf_counter()
         dt, cnt, phases, n_end, tphases = run_tau(ctx, m, r, prompts, ti, a.steps, a.warmup, prof, table_steps if ti == 0 else 0, a.verify)
@@ -260,7 +272,7 @@ def main():
         "dtype": "f32" if m.dtype == "fp32" else "bf16",
         "data": "synthetic",
         "config": {"workload": wl.name, "batch": B, "block_D": D, "tau": main_r["tau"], "paged_kv": bool(r.paged),
-                   "prompt_len": [r.prompt_lo, r.prompt_hi], "kernels": ctx.kernel_info,
+                   "prompt_len": [r.prompt_lo, r.prompt_hi], "kernels": ctx.kernel_info, "graph_replay": bool(a.graph),
                    "decoding": "greedy longest-prefix (gamma_tau)" if a.verify is None else
                                "self-speculative (gamma_verify, rule %d): a step is the block step plus the verification pass" % a.verify},
         "gamma_hist": main_r["hist"],

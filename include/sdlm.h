@@ -139,6 +139,17 @@ int sdlm_prefill(sdlm_ctx *ctx, int32_t batch, const int32_t *ids_packed, const 
 int sdlm_decode_step(sdlm_ctx *ctx, int32_t *ids, int32_t *count, float *conf, float *logits);
 
 /*
+ * Replay the decode step as a HIP graph.  The launch sequence of sdlm_decode_step is fixed once the batch is known
+ * (row counts, lengths and page tables live in device memory), so with enable != 0 the first sdlm_decode_step after
+ * a prefill, or after the output pointers change, captures its launches on the context's stream and later calls
+ * replay the captured graph: one submission instead of ~9 launches per layer, which is what bounds the step for small
+ * batches.  Results are identical to the eager path.  The step runs eagerly regardless while any phase is being
+ * timed (sdlm_profile) or a debug tap is set.  sdlm_verify_step and sdlm_kv_commit are always eager.
+ * Errors: SDLM_ESTATE if the context was created on the null stream (which cannot be captured).
+ */
+int sdlm_graph(sdlm_ctx *ctx, int32_t enable);
+
+/*
  * Second pass of a self-speculative step (Sec. 3.4, "Self-Speculative Decoding", Eq. 10); call it between
  * sdlm_decode_step, whose D arg-max tokens are the speculative tokens yhat^1..yhat^D, and sdlm_kv_commit.
  * Verification input j (j = 2..D) is the sequence extended by yhat^1..yhat^{j-1} followed by the mask tokens, i.e.

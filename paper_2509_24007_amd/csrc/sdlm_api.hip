@@ -156,6 +156,11 @@ struct sdlm_ctx {
     bool prefilled = false, stepped = false;
     std::vector<int32_t> n_ub;           // host upper bound of n_b
     std::vector<Tap> taps;
+    // graph replay of the decode step (opt-in): the launch sequence of a step is fixed once the batch is, all sizes
+    // that vary from step to step live in device memory
+    bool graph_on = false;
+    hipGraphExec_t graph_exec = nullptr;
+    void *graph_key[4] = {nullptr, nullptr, nullptr, nullptr};   // the output pointers baked into the captured launches
     // profiling
     uint32_t prof = 0;                   // bit p: phase p is bracketed by events
     std::vector<hipEvent_t> ev;          // pairs
@@ -295,6 +300,12 @@ void run_lm_head(sdlm_ctx *c, int lm_rows, float *logits)
             launch_lm_reduce(s, z, V, c->ids_rows, c->conf_rows, c->r.conf_fn, c->rm.counts + 2, lm_rows);
         }
     }
+}
+
+void drop_graph(sdlm_ctx *c)
+{
+    if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
+    c->graph_exec = nullptr;
 }
 
 int refresh_lengths(sdlm_ctx *c, int32_t *flags_out)
@@ -470,6 +481,7 @@ int sdlm_prefill(sdlm_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
         return fail(c, SDLM_ECAPACITY, "prompts need %ld pages, the pool has %d", pages_needed, c->L.n_pages);
     c->batch = batch;
     c->prefilled = false; c->stepped = false;
+    drop_graph(c);   // the batch size is baked into the captured launches
     // sequence state
     const int B = c->r.max_batch;
     std::vector<int32_t> n(B, 0), last(B, 0), table((size_t)B * pps, -1), backed(B, 0);
@@ -556,13 +568,43 @@ int sdlm_decode_step(sdlm_ctx *c, int32_t *ids, int32_t *count, float *conf, flo
                 return fail(c, SDLM_ECAPACITY, "sequence %d: %d tokens + block exceed max_seq_len %d", b, c->n_ub[b], c->r.max_seq_len);
     }
     hipStream_t s = c->stream;
-    const int rows = B * 2 * D;
-    { Phase p(c, SDLM_PH_ROWS); launch_assemble_decode(s, c->st, c->rm, B, D, c->m.mask_token_id, c->L.group_rows, c->kg.staging_base, c->m.block_causal); }
-    run_layers(c, rows, B * ((2 * D + c->L.group_rows - 1) / c->L.group_rows));
-    run_lm_head(c, B * D, logits);
-    { Phase p(c, SDLM_PH_ACCEPT); launch_accept(s, c->st, c->ids_rows, c->conf_rows, B, D, c->r.tau, c->r.accept_rule, ids, count, conf); }
+    auto launch_all = [&]() {
+        const int rows = B * 2 * D;
+        { Phase p(c, SDLM_PH_ROWS); launch_assemble_decode(s, c->st, c->rm, B, D, c->m.mask_token_id, c->L.group_rows, c->kg.staging_base, c->m.block_causal); }
+        run_layers(c, rows, B * ((2 * D + c->L.group_rows - 1) / c->L.group_rows));
+        run_lm_head(c, B * D, logits);
+        { Phase p(c, SDLM_PH_ACCEPT); launch_accept(s, c->st, c->ids_rows, c->conf_rows, B, D, c->r.tau, c->r.accept_rule, ids, count, conf); }
+    };
+    if (c->graph_on && c->prof == 0 && c->taps.empty()) {
+        void *key[4] = {ids, count, conf, logits};
+        if (!c->graph_exec || memcmp(key, c->graph_key, sizeof key) != 0) {
+            drop_graph(c);
+            hipGraph_t g = nullptr;
+            HIPCHK(c, hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+            launch_all();
+            hipError_t e1 = hipStreamEndCapture(s, &g);
+            if (e1 != hipSuccess || !g) return fail(c, SDLM_EHIP, "graph capture of the decode step failed: %s", hipGetErrorString(e1));
+            hipError_t e2 = hipGraphInstantiate(&c->graph_exec, g, nullptr, nullptr, 0);
+            (void)hipGraphDestroy(g);
+            if (e2 != hipSuccess) { c->graph_exec = nullptr; return fail(c, SDLM_EHIP, "hipGraphInstantiate: %s", hipGetErrorString(e2)); }
+            memcpy(c->graph_key, key, sizeof key);
+        }
+        HIPCHK(c, hipGraphLaunch(c->graph_exec, s));
+    } else {
+        launch_all();
+    }
     HIPCHK(c, hipGetLastError());
     c->stepped = true;
+    return SDLM_OK;
+}
+
+int sdlm_graph(sdlm_ctx *c, int32_t enable)
+{
+    if (!c) return SDLM_EINVAL;
+    if (enable && c->stream == nullptr)
+        return fail(c, SDLM_ESTATE, "graph replay needs a context created on a stream other than the null stream (it cannot be captured)");
+    c->graph_on = enable != 0;
+    if (!enable) drop_graph(c);
     return SDLM_OK;
 }
 
@@ -704,6 +746,7 @@ void sdlm_destroy(sdlm_ctx *c)
 {
     if (!c) return;
     for (auto e : c->ev) (void)hipEventDestroy(e);
+    drop_graph(c);
     delete c;
 }
 

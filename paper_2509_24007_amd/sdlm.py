@@ -19,7 +19,7 @@ PHASES = ("rows", "norm", "qkv", "rope", "attn", "oproj", "gateup", "down", "lmh
 OK, EINVAL, ECAPACITY, ESTATE, EHIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("sdlm_workspace_bytes", "sdlm_create", "sdlm_init_weights", "sdlm_prefill", "sdlm_decode_step",
-           "sdlm_verify_step", "sdlm_kv_commit", "sdlm_get_lengths", "sdlm_debug_tap", "sdlm_debug_rows", "sdlm_debug_read_kv",
+           "sdlm_graph", "sdlm_verify_step", "sdlm_kv_commit", "sdlm_get_lengths", "sdlm_debug_tap", "sdlm_debug_rows", "sdlm_debug_read_kv",
            "sdlm_max_rows", "sdlm_profile", "sdlm_profile_read", "sdlm_kernel_info", "sdlm_last_error",
            "sdlm_destroy")
 
@@ -70,6 +70,8 @@ def load():
     L.sdlm_prefill.argtypes = [vp, i32, vp, vp]
     L.sdlm_decode_step.restype = C.c_int
     L.sdlm_decode_step.argtypes = [vp, vp, vp, vp, vp]
+    L.sdlm_graph.restype = C.c_int
+    L.sdlm_graph.argtypes = [vp, C.c_int32]
     L.sdlm_verify_step.restype = C.c_int
     L.sdlm_verify_step.argtypes = [vp, C.c_int32, vp, vp, vp]
     L.sdlm_kv_commit.restype = C.c_int
@@ -154,6 +156,13 @@ class Context:
         self._keep: List[object] = []
 
     # -- helpers
+    def _order_inputs(self):
+        """The library runs on the stream the context was created on.  When torch's current stream is another one,
+        work queued there that produces the tensors being handed over must come first."""
+        cur = torch.cuda.current_stream(self.device)
+        if cur.cuda_stream != self.stream.cuda_stream:
+            self.stream.wait_stream(cur)
+
     def _check(self, rc: int):
         if rc != 0:
             raise SdlmError(rc, self.L.sdlm_last_error(self.h).decode())
@@ -207,6 +216,7 @@ class Context:
                 tab[l] = place(t) if t is not None else None
             keep.append(tab)
             setattr(w, name, C.cast(tab, _PP))
+        self._order_inputs()
         self._check(self.L.sdlm_init_weights(self.h, C.byref(w), 1 if on_dev else 0))
 
     def prefill(self, prompts: Sequence) -> None:
@@ -230,6 +240,10 @@ class Context:
                                   logits.is_cuda and logits.is_contiguous())
         self._check(self.L.sdlm_decode_step(self.h, _dp(ids), _dp(count), _dp(conf), _dp(logits)))
 
+    def graph(self, enable: bool = True) -> None:
+        """Replay decode_step as a HIP graph (the context must have been created on a non-default stream)."""
+        self._check(self.L.sdlm_graph(self.h, 1 if enable else 0))
+
     def verify_step(self, rule: int = 0, ids_tilde: Optional[torch.Tensor] = None, count: Optional[torch.Tensor] = None,
                     logits: Optional[torch.Tensor] = None) -> None:
         """Self-speculative verification of the last decode_step; ids_tilde [batch, D] int32, count [batch] int32,
@@ -247,6 +261,7 @@ class Context:
             assert ids_override.dtype == torch.int32 and ids_override.is_cuda and ids_override.is_contiguous()
             assert count_override is not None and count_override.dtype == torch.int32 and count_override.is_cuda
             assert ids_override.numel() >= self.batch * self.D and count_override.numel() >= self.batch
+            self._order_inputs()
         self._check(self.L.sdlm_kv_commit(self.h, _dp(ids_override), _dp(count_override)))
 
     # -- state and debugging

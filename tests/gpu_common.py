@@ -10,10 +10,13 @@ from paper_2509_24007_amd import sdlm
 
 
 def gpu_context(mcfg, g_dev, layers_dev, *, max_batch, max_seq_len, D, tau, paged=False, n_pages=0, conf_fn=0,
-                accept_rule=0, prefill_rows=0):
-    ctx = sdlm.Context(sdlm.model_cfg(mcfg), max_batch=max_batch, max_seq_len=max_seq_len, block_D=D, tau=tau,
-                       paged=paged, n_pages=n_pages, conf_fn=conf_fn, accept_rule=accept_rule, prefill_rows=prefill_rows,
-                       poison=True)
+                accept_rule=0, prefill_rows=0, stream=None):
+    """stream: a torch.cuda.Stream for the library to run on (default: torch's current stream)."""
+    with torch.cuda.stream(stream):
+        ctx = sdlm.Context(sdlm.model_cfg(mcfg), max_batch=max_batch, max_seq_len=max_seq_len, block_D=D, tau=tau,
+                           paged=paged, n_pages=n_pages, conf_fn=conf_fn, accept_rule=accept_rule, prefill_rows=prefill_rows,
+                           poison=True)
+    torch.cuda.synchronize()
     ctx.init_weights(g_dev, {l: layers_dev[l] for l in range(mcfg.n_layers)})
     torch.cuda.synchronize()
     return ctx

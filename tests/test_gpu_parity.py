@@ -394,3 +394,65 @@ def test_block_causal_bf16_mfma():
     st, _ = lockstep(ctx, om, prompts, 4, 0.6, steps, logit_tol=2e-2, conf_tol=1e-3, bf16=True, max_len=max_len, verify_rule=0)
     print("block-causal mfma", st)
     ctx.close()
+
+
+# ------------------------------------------------------------------ HIP-graph replay of the step
+@pytest.mark.parametrize("kind", ["fp32", "mfma"])
+def test_graph_replay_matches_oracle_and_eager(kind):
+    """Every replay is checked against the oracle, with the library's eager commit kernels (own and override) and host
+    synchronisations between replays; then a replayed and an eager context are compared bit for bit."""
+    if kind == "fp32":
+        m, std, tol, ctol, bf = gpu_cfg(), 0.3, 1e-4, 1e-5, False
+    else:
+        m, std, tol, ctol, bf = mfma_cfg(), 0.05, 2e-2, 1e-3, True
+    om, g_dev, layers_dev = both_models(m, seed=8, std=std)
+    lens = [1, 7, 16, 33, 40]
+    D, tau, steps = 4, 0.6, 8
+    prompts = [syn.uniform_int(3, f"gr{i}", n, 0, m.vocab - 1).numpy() for i, n in enumerate(lens)]
+    ovr = syn.make_overrides(12, steps, len(lens), D, m.vocab)
+    max_len = max(lens) + steps * D + D
+    n_pages = sum((n + steps * D + 15) // 16 + 1 for n in lens)
+    side = torch.cuda.Stream()
+    kw = dict(max_batch=len(lens), max_seq_len=max_len, D=D, tau=tau, paged=True, n_pages=n_pages, prefill_rows=64)
+    ctx = gpu_context(m, g_dev, layers_dev, stream=side, **kw)
+    ctx.graph(True)
+    st, _ = lockstep(ctx, om, prompts, D, tau, steps, logit_tol=tol, conf_tol=ctol, overrides=ovr, bf16=bf, max_len=max_len)
+    print("graph", kind, st)
+    # replayed vs eager, same inputs, fresh contexts: identical bits
+    outs = []
+    for use_graph in (True, False):
+        c2 = gpu_context(m, g_dev, layers_dev, stream=side, **kw)
+        if use_graph:
+            c2.graph(True)
+        c2.prefill(prompts)
+        ids = torch.empty(steps, len(lens), D, dtype=torch.int32, device="cuda")
+        cnt = torch.empty(steps, len(lens), dtype=torch.int32, device="cuda")
+        conf = torch.empty(len(lens), D, dtype=torch.float32, device="cuda")
+        logits = torch.empty(len(lens) * D, m.vocab, dtype=torch.float32, device="cuda")
+        torch.cuda.synchronize()
+        trace = []
+        for t in range(steps):
+            c2.decode_step(ids[t], cnt[t], conf, logits) if t % 3 else c2.decode_step(ids[t], cnt[t])   # the outputs change: re-capture
+            torch.cuda.synchronize()
+            trace.append((conf.clone(), logits.clone()) if t % 3 else None)
+            c2.kv_commit()
+        torch.cuda.synchronize()
+        outs.append((ids.cpu(), cnt.cpu(), trace))
+        c2.close()
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
+    for a, b in zip(outs[0][2], outs[1][2]):
+        if a is not None:
+            assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    ctx.close()
+
+
+def test_graph_needs_a_real_stream():
+    m = gpu_cfg()
+    om, g_dev, layers_dev = both_models(m, seed=8, std=0.3)
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=1, max_seq_len=32, D=2, tau=0.5)
+    from paper_2509_24007_amd.sdlm import SdlmError
+    if ctx.stream.cuda_stream == 0:
+        with pytest.raises(SdlmError):
+            ctx.graph(True)
+    ctx.graph(False)
+    ctx.close()
