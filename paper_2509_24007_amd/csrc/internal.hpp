@@ -98,6 +98,7 @@ struct GemmArgs {
     const int32_t *pR;  // device row count
     int max_rows, N, K;
     float scale;
+    int min_rows;       // host-known lower bound of the device row count (0: unknown); only steers the launch shape
 };
 
 void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows,

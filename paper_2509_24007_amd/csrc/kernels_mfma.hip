@@ -65,6 +65,7 @@ struct MfmaArgs {
     float4 *lm_part;    // LM head: [n_blocks][max_rows] partial (max, sum, entropy sum, argmax bits)
     const int32_t *pR;
     int max_rows, N, K, n_tiles, n_blocks, m_blocks, splits, stages_per_split, n_out;   // n_out: row length of the destination
+    int m_sure;         // row blocks below this index certainly hold rows; they come first in the grid
     size_t slab;        // elements between split-k slabs
     float scale;
 };
@@ -84,11 +85,22 @@ __global__ __launch_bounds__(256, (w_sets<MT, NT>() == 2 ? 2 : 1)) void gemm_mfm
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps the weight stream's base in SGPRs
     const int R = min(*a.pR, a.max_rows);
-    // workgroup id -> tile: ids that land on one XCD (id % 8) get consecutive tiles
-    const int per = gridDim.x >> 3;
-    const int t = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
-    if (t >= a.n_blocks * a.m_blocks * a.splits) return;
-    const int mblk = t % a.m_blocks, split = (t / a.m_blocks) % a.splits, nblk = t / (a.m_blocks * a.splits);
+    // workgroup id -> tile.  The grid has two parts: the row blocks that certainly hold rows (mblk < m_sure), then the
+    // others, which usually exit at once; mixing them would leave the compute units that draw an empty block idle.
+    // Within a part, ids that land on one XCD (id % 8) get consecutive tiles, the row blocks of one weight band first.
+    const int n_first = a.n_blocks * a.splits * a.m_sure, first8 = (n_first + 7) & ~7;
+    int mblk, rest;
+    if ((int)blockIdx.x < first8) {
+        const int per = first8 >> 3, t = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+        if (t >= n_first) return;
+        mblk = t % a.m_sure; rest = t / a.m_sure;
+    } else {
+        const int bid = blockIdx.x - first8, m_rest = a.m_blocks - a.m_sure;
+        const int per = (gridDim.x - first8) >> 3, t = (bid & 7) * per + (bid >> 3);
+        if (t >= a.n_blocks * a.splits * m_rest) return;
+        mblk = a.m_sure + t % m_rest; rest = t / m_rest;
+    }
+    const int split = rest % a.splits, nblk = rest / a.splits;
     const int m0 = mblk * MT * 32;
     if (m0 >= R) return;
     const int KS = a.K >> 4, S = a.K >> 6;
@@ -434,43 +446,59 @@ __global__ __launch_bounds__(256) void lm_combine_k(const float4 *part, int n_bl
 // ------------------------------------------------------------------------------------------------ launch policy
 struct TileChoice { int MT, NT, splits; };
 
-static TileChoice choose(int epi, int rows, int N, int K, size_t slab_room_floats)
+static int sure_blocks(int rows, int min_rows, int MT)
+{
+    const int mb = (rows + MT * 32 - 1) / (MT * 32);
+    if (min_rows <= 0) return mb;
+    const int ms = (min_rows + MT * 32 - 1) / (MT * 32);
+    return ms < 1 ? 1 : (ms > mb ? mb : ms);
+}
+
+// rows: bound of the launch (grid); min_rows: rows that are certainly there.
+static TileChoice choose(int epi, int rows, int min_rows, int N, int K, size_t slab_room_floats)
 {
     TileChoice c;
     c.MT = rows <= 32 ? 1 : rows <= 64 ? 2 : 4;
     c.NT = 2;
-    if (epi != EPI_SWIGLU && epi != EPI_LMHEAD) {
+    if (epi != EPI_SWIGLU && epi != EPI_LMHEAD && c.MT < 4) {
         int mb = (rows + c.MT * 32 - 1) / (c.MT * 32);
         if ((long)((N + 255) / 256) * mb < 256) c.NT = 1;
     }
     c.splits = 1;
     if (epi == EPI_STORE_F32 || epi == EPI_RESID) {
-        int bn = 128 * c.NT, mb = (rows + c.MT * 32 - 1) / (c.MT * 32);
-        long wgs = (long)((N + bn - 1) / bn) * mb;
-        int S = K / 64, want = (int)((512 + wgs - 1) / wgs);
-        int cap_k = S / 4 > 0 ? S / 4 : 1;                             // at least 4 stages (256 deep) per split
-        long cap_m = (long)(slab_room_floats / ((size_t)rows * N));    // slabs must fit the scratch area
-        int sp = want;
-        if (sp > cap_k) sp = cap_k;
-        if (sp > cap_m) sp = (int)cap_m;
-        if (sp > 16) sp = 16;
-        if (sp < 1) sp = 1;
-        if ((size_t)rows * N * 4 * sp > (size_t)8 << 20 && wgs >= 128) sp = sp > 2 ? 2 : sp;   // many rows: slab traffic outweighs the gain
-        c.splits = sp;
+        const int S = K / 64;
+        const int cap_k = S / 4 > 0 ? S / 4 : 1;                             // at least 4 stages (256 deep) per split
+        const long cap_m = (long)(slab_room_floats / ((size_t)rows * N));    // slabs must fit the scratch area
+        auto clamp = [&](long sp) { sp = sp > cap_k ? cap_k : sp; sp = sp > cap_m ? cap_m : sp; sp = sp > 16 ? 16 : sp; return (int)(sp < 1 ? 1 : sp); };
+        if (c.MT == 4) {
+            // Workgroups are dealt out to the compute units round robin and two heavy ones on one unit take twice as
+            // long as one: the fastest shape is one workgroup on as many units as possible, i.e. the largest split
+            // count that keeps (column blocks x occupied row blocks x splits) within the 256 units.  The 256-wide
+            // tile is the more efficient one; the 128-wide tile takes over when the wide one would leave more
+            // than a quarter of the units without work.
+            const long ms = sure_blocks(rows, min_rows, c.MT), nb2 = (N + 255) / 256, nb1 = (N + 127) / 128;
+            const int sp2 = clamp(256 / (nb2 * ms));
+            if (nb2 * ms * sp2 >= 192) { c.NT = 2; c.splits = sp2; }
+            else { c.NT = 1; c.splits = clamp(256 / (nb1 * ms)); }
+        } else {
+            const long wgs = (long)((N + 128 * c.NT - 1) / (128 * c.NT)) * ((rows + c.MT * 32 - 1) / (c.MT * 32));
+            c.splits = clamp((512 + wgs - 1) / wgs);
+        }
     }
     return c;
 }
 
 template <int EPI>
-static void launch_cfg(hipStream_t s, const TileChoice &c, MfmaArgs &a)
+static void launch_cfg(hipStream_t s, const TileChoice &c, MfmaArgs &a, int min_rows)
 {
     a.n_blocks = (a.n_tiles + 4 * c.NT - 1) / (4 * c.NT);
     a.m_blocks = (a.max_rows + c.MT * 32 - 1) / (c.MT * 32);
     a.splits = c.splits;
     int S = a.K / 64;
     a.stages_per_split = (S + c.splits - 1) / c.splits;
-    int tiles = a.n_blocks * a.m_blocks * a.splits;
-    dim3 grid((tiles + 7) / 8 * 8), block(256);
+    a.m_sure = sure_blocks(a.max_rows, min_rows, c.MT);
+    const int first = a.n_blocks * a.splits * a.m_sure, rest = a.n_blocks * a.splits * (a.m_blocks - a.m_sure);
+    dim3 grid((first + 7) / 8 * 8 + (rest + 7) / 8 * 8), block(256);
 #define SDLM_GO(MT_, NT_) hipLaunchKernelGGL((gemm_mfma_k<MT_, NT_, EPI>), grid, block, 0, s, a)
     if (EPI == EPI_SWIGLU || EPI == EPI_LMHEAD || c.NT == 2) {
         if (c.MT == 1) SDLM_GO(1, 2); else if (c.MT == 2) SDLM_GO(2, 2); else SDLM_GO(4, 2);
@@ -491,28 +519,28 @@ int launch_gemm_mfma(hipStream_t s, int epi, const GemmArgs &g, float *slabs, si
     a.Yf = g.Yf; a.Yt = (bf16_t *)g.Yt; a.pR = g.pR; a.max_rows = g.max_rows; a.N = g.N; a.K = g.K; a.scale = g.scale;
     a.n_out = g.N;
     a.n_tiles = epi == EPI_SWIGLU ? 2 * (int)(mfma_pad_n(g.N) / 32) : (int)(mfma_pad_n(g.N) / 32);
-    TileChoice c = choose(epi, g.max_rows, g.N, g.K, slab_room_floats);
+    TileChoice c = choose(epi, g.max_rows, g.min_rows, g.N, g.K, slab_room_floats);
     a.slab = (size_t)g.max_rows * g.N;
     if (c.splits > 1) a.Yf = slabs;
     switch (epi) {
-    case EPI_STORE_F32: launch_cfg<EPI_STORE_F32>(s, c, a); break;
-    case EPI_RESID: launch_cfg<EPI_RESID>(s, c, a); break;
-    default: launch_cfg<EPI_SWIGLU>(s, c, a); break;
+    case EPI_STORE_F32: launch_cfg<EPI_STORE_F32>(s, c, a, g.min_rows); break;
+    case EPI_RESID: launch_cfg<EPI_RESID>(s, c, a, g.min_rows); break;
+    default: launch_cfg<EPI_SWIGLU>(s, c, a, g.min_rows); break;
     }
     if (c.splits > 1 && epi == EPI_RESID && !defer_reduce)
         hipLaunchKernelGGL(reduce_slabs_k, dim3(g.max_rows), dim3(256), 0, s, g.Yf, slabs, c.splits, a.slab, g.N, g.pR, g.max_rows);
     return c.splits;   // slabs left for the consumer: always for STORE_F32, for RESID when defer_reduce
 }
 
-void launch_lmhead_mfma(hipStream_t s, const void *xhat, const void *w_packed, const int32_t *p_rows, int max_rows, int V, int h, float scale,
+void launch_lmhead_mfma(hipStream_t s, const void *xhat, const void *w_packed, const int32_t *p_rows, int max_rows, int min_rows, int V, int h, float scale,
                         int conf_fn, float *logits_out, void *scratch, int32_t *ids, float *conf)
 {
     MfmaArgs a{};
     a.X = (const bf16_t *)xhat; a.Wp = (const bf16_t *)w_packed; a.pR = p_rows; a.max_rows = max_rows; a.N = V; a.K = h; a.scale = scale;
     a.n_out = V; a.logits = logits_out; a.lm_part = (float4 *)scratch;
     a.n_tiles = (int)(mfma_pad_n(V) / 32);
-    TileChoice c = choose(EPI_LMHEAD, max_rows, V, h, 0);
-    launch_cfg<EPI_LMHEAD>(s, c, a);
+    TileChoice c = choose(EPI_LMHEAD, max_rows, min_rows, V, h, 0);
+    launch_cfg<EPI_LMHEAD>(s, c, a, min_rows);
     hipLaunchKernelGGL(lm_combine_k, dim3(max_rows), dim3(256), 0, s, (const float4 *)scratch, a.n_blocks, max_rows, p_rows, V, conf_fn, ids, conf);
 }
 

@@ -27,7 +27,7 @@ void launch_pack_mfma(hipStream_t s, void *dst, const void *src, int N, int K, i
 int launch_gemm_mfma(hipStream_t s, int epi, const GemmArgs &a, float *slabs, size_t slab_room_floats, bool defer_reduce);
 void launch_attn_mfma(hipStream_t s, const sdlm_model_cfg *m, int max_seq_len, const void *q, void *out, const void *pool_layer,
                       const KvGeom &kg, const RowMeta &rm, const SeqState &st, int D, int max_groups, void *scratch, size_t scratch_bytes);
-void launch_lmhead_mfma(hipStream_t s, const void *xhat, const void *w_packed, const int32_t *p_rows, int max_rows, int V, int h,
+void launch_lmhead_mfma(hipStream_t s, const void *xhat, const void *w_packed, const int32_t *p_rows, int max_rows, int min_rows, int V, int h,
                         float scale, int conf_fn, float *logits_out, void *scratch, int32_t *ids, float *conf);
 
 }  // namespace sdlm

@@ -121,7 +121,7 @@ void plan(const sdlm_model_cfg *m, const sdlm_run_cfg *r, Layout *L)
     L->ids_rows = take((size_t)B * D * 4);
     L->attn_bytes = L->mfma ? mfma_attn_scratch_bytes(m, r, L->max_rows) : 256;
     L->attn_part = take(L->attn_bytes);
-    L->slab_floats = L->mfma ? ((size_t)8 << 20) : 64;                       // 32 MB of split-k slabs
+    L->slab_floats = L->mfma ? ((size_t)16 << 20) : 64;                      // 64 MB of split-k slabs
     L->slabs = take(L->slab_floats * 4);
     L->lm_part = take(L->mfma ? mfma_lm_scratch_bytes(m->vocab, B * D) : 256);
     L->group_rows = L->mfma ? mfma_group_rows(m) : GROUP_ROWS;
@@ -219,8 +219,8 @@ void run_taps(sdlm_ctx *c, int layer, int which, const void *src, size_t bytes)
 }
 
 // The decoder layers over the rows described by c->rm.  `rows` bounds the launch grids (the device-side row
-// count decides what is computed).
-void run_layers(sdlm_ctx *c, int rows, int groups)
+// count decides what is computed); `rows_sure` is a host-known lower bound of that count (it only steers launch shapes).
+void run_layers(sdlm_ctx *c, int rows, int groups, int rows_sure)
 {
     const sdlm_model_cfg &m = c->m;
     const int dt = m.dtype, h = m.hidden, F = m.ffn, d = m.head_dim;
@@ -237,7 +237,7 @@ void run_layers(sdlm_ctx *c, int rows, int groups)
         int qkv_slabs = 1;
         {
             Phase p(c, SDLM_PH_QKV);
-            GemmArgs a{c->xn, w.wqkv, nullptr, m.has_qkv_bias ? w.bqkv : nullptr, c->qkv, nullptr, c->rm.counts, rows, nqkv, h, 1.f};
+            GemmArgs a{c->xn, w.wqkv, nullptr, m.has_qkv_bias ? w.bqkv : nullptr, c->qkv, nullptr, c->rm.counts, rows, nqkv, h, 1.f, rows_sure};
             if (c->L.mfma) qkv_slabs = launch_gemm_mfma(s, EPI_STORE_F32, a, c->slabs, c->L.slab_floats, false); else launch_gemm_generic(s, dt, EPI_STORE_F32, a);
         }
         {
@@ -253,7 +253,7 @@ void run_layers(sdlm_ctx *c, int rows, int groups)
         run_taps(c, l, 1, c->att, (size_t)rows * nq * e);
         {
             Phase p(c, SDLM_PH_OPROJ);
-            GemmArgs a{c->att, w.wo, nullptr, nullptr, c->x, nullptr, c->rm.counts, rows, h, nq, 1.f};
+            GemmArgs a{c->att, w.wo, nullptr, nullptr, c->x, nullptr, c->rm.counts, rows, h, nq, 1.f, rows_sure};
             if (c->L.mfma) {
                 // the split-k partial sums of a residual projection are added by the next RMSNorm (unless a tap wants x now)
                 int sp = launch_gemm_mfma(s, EPI_RESID, a, c->slabs, c->L.slab_floats, c->taps.empty());
@@ -264,13 +264,13 @@ void run_layers(sdlm_ctx *c, int rows, int groups)
         { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xn, c->x, w.ffn_norm, h, m.rms_eps, nullptr, c->rm.counts, rows, c->slabs, c->pend_slabs, c->pend_stride); c->pend_slabs = 0; }
         {
             Phase p(c, SDLM_PH_GATEUP);
-            GemmArgs a{c->xn, w.w_gate, w.w_up, nullptr, nullptr, c->act, c->rm.counts, rows, F, h, 1.f};
+            GemmArgs a{c->xn, w.w_gate, w.w_up, nullptr, nullptr, c->act, c->rm.counts, rows, F, h, 1.f, rows_sure};
             if (c->L.mfma) launch_gemm_mfma(s, EPI_SWIGLU, a, c->slabs, c->L.slab_floats, false); else launch_gemm_generic(s, dt, EPI_SWIGLU, a);
         }
         run_taps(c, l, 2, c->act, (size_t)rows * F * e);
         {
             Phase p(c, SDLM_PH_DOWN);
-            GemmArgs a{c->act, w.w_down, nullptr, nullptr, c->x, nullptr, c->rm.counts, rows, h, F, 1.f};
+            GemmArgs a{c->act, w.w_down, nullptr, nullptr, c->x, nullptr, c->rm.counts, rows, h, F, 1.f, rows_sure};
             if (c->L.mfma) {
                 // the split-k partial sums of a residual projection are added by the next RMSNorm (unless a tap wants x now)
                 int sp = launch_gemm_mfma(s, EPI_RESID, a, c->slabs, c->L.slab_floats, c->taps.empty());
@@ -291,7 +291,7 @@ void run_lm_head(sdlm_ctx *c, int lm_rows, float *logits)
     {
         Phase p(c, SDLM_PH_LMHEAD);
         if (c->L.mfma) {
-            launch_lmhead_mfma(s, c->xhat, c->lm_head, c->rm.counts + 2, lm_rows, V, h, c->m.logit_scale, c->r.conf_fn, logits, c->lm_part,
+            launch_lmhead_mfma(s, c->xhat, c->lm_head, c->rm.counts + 2, lm_rows, lm_rows, V, h, c->m.logit_scale, c->r.conf_fn, logits, c->lm_part,
                                c->ids_rows, c->conf_rows);
         } else {
             float *z = logits ? logits : c->logits;
@@ -534,7 +534,7 @@ int sdlm_prefill(sdlm_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
         HIPCHK(c, hipMemcpyAsync(c->rm.grp_n, gn.data(), gn.size() * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.grp_seq, gs.data(), gs.size() * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.counts, counts, sizeof counts, hipMemcpyHostToDevice, s));
-        run_layers(c, R, (int)g0.size());
+        run_layers(c, R, (int)g0.size(), R);
         HIPCHK(c, hipStreamSynchronize(s));   // the host vectors are reused
         tok.clear(); pos.clear(); seq.clear(); kind.clear(); lim.clear(); g0.clear(); gn.clear(); gs.clear();
         return SDLM_OK;
@@ -571,7 +571,7 @@ int sdlm_decode_step(sdlm_ctx *c, int32_t *ids, int32_t *count, float *conf, flo
     auto launch_all = [&]() {
         const int rows = B * 2 * D;
         { Phase p(c, SDLM_PH_ROWS); launch_assemble_decode(s, c->st, c->rm, B, D, c->m.mask_token_id, c->L.group_rows, c->kg.staging_base, c->m.block_causal); }
-        run_layers(c, rows, B * ((2 * D + c->L.group_rows - 1) / c->L.group_rows));
+        run_layers(c, rows, B * ((2 * D + c->L.group_rows - 1) / c->L.group_rows), B * (D + 1));   // every sequence has >= 1 pending row
         run_lm_head(c, B * D, logits);
         { Phase p(c, SDLM_PH_ACCEPT); launch_accept(s, c->st, c->ids_rows, c->conf_rows, B, D, c->r.tau, c->r.accept_rule, ids, count, conf); }
     };
@@ -624,7 +624,7 @@ int sdlm_verify_step(sdlm_ctx *c, int32_t rule, int32_t *ids_tilde, int32_t *cou
         int groups = 0;
         for (int j = 2; j <= D; ++j) groups += (j - 2 + D + gr - 1) / gr;
         { Phase p(c, SDLM_PH_ROWS); launch_assemble_verify(s, c->st, c->rm, B, D, c->m.mask_token_id, gr, c->kg.staging_base, c->m.block_causal); }
-        run_layers(c, rows, B * groups);
+        run_layers(c, rows, B * groups, rows);
         run_lm_head(c, B * (D - 1), logits);
     }
     { Phase p(c, SDLM_PH_ACCEPT); launch_verify_accept(s, c->st, c->ids_rows, B, D, rule, ids_tilde, count); }
