@@ -456,3 +456,26 @@ def test_graph_needs_a_real_stream():
             ctx.graph(True)
     ctx.graph(False)
     ctx.close()
+
+
+def test_mfma_row_blocks_beyond_the_sure_ones():
+    """Every sequence is forced to accept D tokens, so the next step has the maximum B*2D rows: the row blocks the
+    launch lists last (those that may be empty) all hold rows.  Alternating with single-token commits exercises the
+    ragged and the empty case of the same launch shape."""
+    m = mfma_cfg(n_q_heads=8, n_kv_heads=2)
+    om, g_dev, layers_dev = both_models(m, seed=21, std=0.05)
+    B, D, steps = 24, 4, 6
+    lens = [3 + 5 * i for i in range(B)]
+    prompts = [syn.uniform_int(4, f"rb{i}", n, 0, m.vocab - 1).numpy() for i, n in enumerate(lens)]
+    ids, cnt = syn.make_overrides(14, steps, B, D, m.vocab)
+    cnt = cnt.clone()
+    for t in range(steps):
+        cnt[t] = D if (t // 2) % 2 == 0 else 1       # lockstep applies the overrides on odd steps
+    max_len = max(lens) + steps * D + D
+    n_pages = sum((n + steps * D + 15) // 16 + 1 for n in lens)
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=B, max_seq_len=max_len, D=D, tau=0.6, paged=True, n_pages=n_pages,
+                      prefill_rows=128)
+    assert ctx.kernel_info == "mfma-bf16"
+    st, _ = lockstep(ctx, om, prompts, D, 0.6, steps, logit_tol=2e-2, conf_tol=1e-3, overrides=(ids, cnt), bf16=True, max_len=max_len)
+    print("row blocks", st)
+    ctx.close()
