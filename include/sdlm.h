@@ -222,7 +222,7 @@ int32_t sdlm_max_rows(const sdlm_ctx *ctx);
  * returns, for phase p in 0..SDLM_N_PHASES-1, total milliseconds in ms[p] and launches in launches[p] ([host]).
  */
 enum { SDLM_PH_ROWS = 0, SDLM_PH_NORM, SDLM_PH_QKV, SDLM_PH_ROPE, SDLM_PH_ATTN, SDLM_PH_OPROJ, SDLM_PH_GATEUP,
-       SDLM_PH_DOWN, SDLM_PH_LMHEAD, SDLM_PH_ACCEPT, SDLM_N_PHASES };
+       SDLM_PH_DOWN, SDLM_PH_LMHEAD, SDLM_PH_ACCEPT, SDLM_PH_ATTN_MERGE /* merge of the split-KV partials */, SDLM_N_PHASES };
 int sdlm_profile(sdlm_ctx *ctx, int32_t mask);
 int sdlm_profile_read(sdlm_ctx *ctx, float *ms, int32_t *launches);
 

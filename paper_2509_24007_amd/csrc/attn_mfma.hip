@@ -286,8 +286,9 @@ size_t mfma_attn_scratch_bytes(const sdlm_model_cfg *m, const sdlm_run_cfg *r, i
     return worst * ((size_t)QMAX * HD * 4 + QMAX * 8) + 256;
 }
 
-void launch_attn_mfma(hipStream_t s, const sdlm_model_cfg *m, int max_seq_len, const void *q, void *out, const void *pool_layer,
-                      const KvGeom &kg, const RowMeta &rm, const SeqState &st, int D, int max_groups, void *scratch, size_t scratch_bytes)
+bool launch_attn_mfma(hipStream_t s, const sdlm_model_cfg *m, int max_seq_len, const void *q, void *out, const void *pool_layer,
+                      const KvGeom &kg, const RowMeta &rm, const SeqState &st, int D, int max_groups, void *scratch, size_t scratch_bytes,
+                      int part)
 {
     AttnArgs a;
     a.q = (const bf16_t *)q; a.out = (bf16_t *)out; a.pool = (const bf16_t *)pool_layer;
@@ -303,9 +304,9 @@ void launch_attn_mfma(hipStream_t s, const sdlm_model_cfg *m, int max_seq_len, c
     a.part_o = (float *)scratch;
     a.part_ml = (float2 *)((char *)scratch + items * QMAX * HD * 4);
     a.c = 1.4426950408889634f / sqrtf((float)HD);
-    hipLaunchKernelGGL(attn_mfma_k, dim3(max_groups, kg.n_kv_heads, a.max_chunks), dim3(256), 0, s, a);
-    if (a.max_chunks > 1)
-        hipLaunchKernelGGL(attn_combine_k, dim3(max_groups, kg.n_kv_heads, NQ), dim3(256), 0, s, a);
+    if (part == 0) hipLaunchKernelGGL(attn_mfma_k, dim3(max_groups, kg.n_kv_heads, a.max_chunks), dim3(256), 0, s, a);
+    else if (a.max_chunks > 1) hipLaunchKernelGGL(attn_combine_k, dim3(max_groups, kg.n_kv_heads, NQ), dim3(256), 0, s, a);
+    return a.max_chunks > 1;
 }
 
 }  // namespace sdlm

@@ -25,8 +25,11 @@ void launch_pack_mfma(hipStream_t s, void *dst, const void *src, int N, int K, i
 // EPI_STORE_F32 the consumer always adds the slabs; for EPI_RESID the slabs are added to a.Yf here unless
 // defer_reduce, in which case the next RMSNorm adds them (slab stride = a.max_rows * a.N floats).
 int launch_gemm_mfma(hipStream_t s, int epi, const GemmArgs &a, float *slabs, size_t slab_room_floats, bool defer_reduce);
-void launch_attn_mfma(hipStream_t s, const sdlm_model_cfg *m, int max_seq_len, const void *q, void *out, const void *pool_layer,
-                      const KvGeom &kg, const RowMeta &rm, const SeqState &st, int D, int max_groups, void *scratch, size_t scratch_bytes);
+// part 0: the attention kernel; part 1: the merge of the split-KV partials (a no-op when the launch has a single
+// chunk).  Returns whether the launch shape needs the merge.
+bool launch_attn_mfma(hipStream_t s, const sdlm_model_cfg *m, int max_seq_len, const void *q, void *out, const void *pool_layer,
+                      const KvGeom &kg, const RowMeta &rm, const SeqState &st, int D, int max_groups, void *scratch, size_t scratch_bytes,
+                      int part);
 void launch_lmhead_mfma(hipStream_t s, const void *xhat, const void *w_packed, const int32_t *p_rows, int max_rows, int min_rows, int V, int h,
                         float scale, int conf_fn, float *logits_out, void *scratch, int32_t *ids, float *conf);
 

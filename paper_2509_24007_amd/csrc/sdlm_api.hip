@@ -245,10 +245,15 @@ void run_layers(sdlm_ctx *c, int rows, int groups, int rows_sure)
             launch_rope_scatter(s, dt, qkv_slabs > 1 ? c->slabs : c->qkv, qkv_slabs, (size_t)rows * nqkv, c->q, pool_l, c->kg, c->rm, c->st, c->rope, m.n_q_heads, rows);
         }
         run_taps(c, l, 5, c->q, (size_t)rows * nq * e);
+        bool merge = false;
         {
             Phase p(c, SDLM_PH_ATTN);
-            if (c->L.mfma) launch_attn_mfma(s, &c->m, c->r.max_seq_len, c->q, c->att, pool_l, c->kg, c->rm, c->st, c->r.block_D, groups, c->attn_part, c->L.attn_bytes);
+            if (c->L.mfma) merge = launch_attn_mfma(s, &c->m, c->r.max_seq_len, c->q, c->att, pool_l, c->kg, c->rm, c->st, c->r.block_D, groups, c->attn_part, c->L.attn_bytes, 0);
             else launch_attn_generic(s, dt, c->q, c->att, pool_l, c->kg, c->rm, c->st, m.n_q_heads, rows);
+        }
+        if (merge) {
+            Phase p(c, SDLM_PH_ATTN_MERGE);
+            launch_attn_mfma(s, &c->m, c->r.max_seq_len, c->q, c->att, pool_l, c->kg, c->rm, c->st, c->r.block_D, groups, c->attn_part, c->L.attn_bytes, 1);
         }
         run_taps(c, l, 1, c->att, (size_t)rows * nq * e);
         {

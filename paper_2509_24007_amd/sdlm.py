@@ -15,7 +15,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsdlm.so")
 
-PHASES = ("rows", "norm", "qkv", "rope", "attn", "oproj", "gateup", "down", "lmhead", "accept")
+PHASES = ("rows", "norm", "qkv", "rope", "attn", "oproj", "gateup", "down", "lmhead", "accept", "attn_merge")
 OK, EINVAL, ECAPACITY, ESTATE, EHIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("sdlm_workspace_bytes", "sdlm_create", "sdlm_init_weights", "sdlm_prefill", "sdlm_decode_step",
