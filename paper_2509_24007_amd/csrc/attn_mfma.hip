@@ -89,13 +89,13 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
     float m_run = -INFINITY, l_run = 0.f;
 
     // K/V of one tile pair (32 keys, 16 KB) is fetched by the whole workgroup, 64 bytes per thread, and shared
-    // through LDS in the cache's own operand order; two LDS buffers, the next pair rides in registers meanwhile.
+    // through LDS in the cache's own operand order; two LDS buffers, the next two pairs ride in registers meanwhile.
     __shared__ __attribute__((aligned(16))) bf16_t kv[2][2][2 * PAGE * HD];   // [buffer][tile A/B][K block | V block]
     const int32_t *ptab = a.st.page_table + (size_t)b * a.kg.pages_per_seq;
     const size_t tile_elems = 2 * PAGE * HD;
     const int stg_page = max(a.rm.grp_stg[g], 0);
-    u32x4 r[4];
-    auto fetch = [&](int pp) {
+    u32x4 rA[4], rB[4];   // two tile pairs in flight: the next one and the one after it
+    auto fetch = [&](int pp, u32x4 (&r)[4]) {
         const int uA = 2 * pp, uB = 2 * pp + 1;
         const int pgA = uA >= n_cache ? stg_page : ptab[c0 + uA];
         const int pgB = uB >= nv ? pgA : (uB >= n_cache ? stg_page : ptab[c0 + uB]);
@@ -106,18 +106,13 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
         r[2] = *(const u32x4 *)(tB + tid * 8);
         r[3] = *(const u32x4 *)(tB + (256 + tid) * 8);
     };
-    auto stash = [&](int buf) {
+    auto stash = [&](int buf, const u32x4 (&r)[4]) {
         *(u32x4 *)(&kv[buf][0][0] + tid * 8) = r[0];
         *(u32x4 *)(&kv[buf][0][0] + (256 + tid) * 8) = r[1];
         *(u32x4 *)(&kv[buf][1][0] + tid * 8) = r[2];
         *(u32x4 *)(&kv[buf][1][0] + (256 + tid) * 8) = r[3];
     };
-    fetch(0);
-    stash(0);
-    __syncthreads();
-    for (int pp = 0; pp < n_pairs; ++pp) {
-        const int buf = pp & 1;
-        if (pp + 1 < n_pairs) fetch(pp + 1);
+    auto compute = [&](int pp, int buf) {
         if (wave_active) {
             const int uA = 2 * pp, uB = 2 * pp + 1;
             const bool hasB = uB < nv;
@@ -179,7 +174,21 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
                 O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vo.v, pop.v, O[dt], 0, 0, 0);
             }
         }
-        if (pp + 1 < n_pairs) stash(buf ^ 1);
+    };
+    fetch(0, rA);
+    stash(0, rA);
+    if (n_pairs > 1) fetch(1, rA);
+    __syncthreads();
+    // iteration pp: regs hold pair pp+1, pair pp+2 is requested, pair pp is consumed from LDS
+    for (int pp = 0; pp < n_pairs; pp += 2) {
+        if (pp + 2 < n_pairs) fetch(pp + 2, rB);
+        compute(pp, 0);
+        if (pp + 1 < n_pairs) stash(1, rA);
+        __syncthreads();
+        if (pp + 1 >= n_pairs) break;
+        if (pp + 3 < n_pairs) fetch(pp + 3, rA);
+        compute(pp + 1, 1);
+        if (pp + 2 < n_pairs) stash(0, rB);
         __syncthreads();
     }
     if (!qvalid) return;
