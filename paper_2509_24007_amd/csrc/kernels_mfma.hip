@@ -13,7 +13,8 @@
 //     buffered, rows padded to 144 bytes so that the 16-byte operand reads do not collide on banks).
 //   * Skinny problems (few rows, few output features) are split along k; the partial sums go to a scratch
 //     slab per split and are added in a fixed order by the consumer, so results do not depend on timing.
-//   * Workgroup ids are remapped so that the row blocks of one weight band run on the same XCD and share its L2.
+//   * Workgroup ids are remapped so that the row blocks of one weight band run on the same XCD and share its L2,
+//     and so that the row blocks which may be empty come last in the grid (see the kernel).
 #include "mfma.hpp"
 
 namespace sdlm {
@@ -132,11 +133,13 @@ __global__ __launch_bounds__(256, (w_sets<MT, NT>() == 2 ? 2 : 1)) void gemm_mfm
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[nt][mt][v] = 0.f;
 
-    // Software pipeline: the weight operands of slice s+2 and the activation slice s+1 are requested at the top of
-    // slice s.  Three rotating register sets hold the weights (the loop is unrolled by three so that the sets keep
-    // static names); the activations go registers -> LDS at the bottom of the slice.  Activation loads are issued
-    // before the weight loads: the counter that orders returns is in program order, so waiting for the (L2-hot)
-    // activations leaves the (HBM) weight loads in flight.
+    // Software pipeline.  Small tiles (MT < 4): three rotating weight register sets, the weights of slice s+2 and the
+    // activations of slice s+1 are requested at the top of slice s (the loop is unrolled by three so that the sets keep
+    // static names).  128-row tiles: two weight sets and one activation operand set, so that accumulators + operands
+    // fit in 256 registers and two workgroups share a compute unit; the loads of slice s+1 are spread over slice s.
+    // In both, the activations go registers -> LDS at the bottom of the slice, and activation loads are issued before
+    // weight loads: the counter that orders returns is in program order, so waiting for the (L2-hot) activations
+    // leaves the (HBM) weight loads in flight.
     bf16x8 w0[NT][4], w1[NT][4], w2[w_sets<MT, NT>() == 3 ? NT : 1][4];
     u32x4 xr[MT];
     const int s_last = s_end - 1;
