@@ -77,10 +77,10 @@ __device__ inline float silu_f(float v) { return v / (1.0f + __expf(-v)); }
 
 // The largest tile keeps two register sets of weights instead of three so that accumulators + operands fit in 256
 // registers: two workgroups then share a compute unit and one's barrier and load waits are covered by the other.
-template <int MT, int NT> constexpr int w_sets() { return (MT == 4) ? 2 : 3; }
+template <int MT, int NT> constexpr int w_sets() { return (MT >= 4) ? 2 : 3; }
 
 template <int MT, int NT, int EPI>
-__global__ __launch_bounds__(256, (w_sets<MT, NT>() == 2 ? 2 : 1)) void gemm_mfma_k(MfmaArgs a)
+__global__ __launch_bounds__(256, (MT == 4 ? 2 : 1)) void gemm_mfma_k(MfmaArgs a)
 {
     __shared__ __attribute__((aligned(16))) bf16_t Xs[2][MT * 32][XS_STRIDE];
     const int tid = threadIdx.x, lane = tid & 63;
@@ -201,7 +201,8 @@ __global__ __launch_bounds__(256, (w_sets<MT, NT>() == 2 ? 2 : 1)) void gemm_mfm
         __builtin_amdgcn_sched_group_barrier(0x100, (reload) ? 1 : 0, 0);                                         \
     }
 #define SDLM_KSTEP2(WC, ks, reload)                                                                               \
-    SDLM_SLOT(WC, ks, 0, reload) SDLM_SLOT(WC, ks, 1, reload) SDLM_SLOT(WC, ks, 2, reload) SDLM_SLOT(WC, ks, 3, reload)
+    SDLM_SLOT(WC, ks, 0, reload) SDLM_SLOT(WC, ks, 1, reload) SDLM_SLOT(WC, ks, 2, reload) SDLM_SLOT(WC, ks, 3, reload) \
+    SDLM_SLOT(WC, ks, 4, reload) SDLM_SLOT(WC, ks, 5, reload)
 #define SDLM_STAGE2(WC, WN, stage)                                                                                \
     {                                                                                                             \
         SDLM_LOAD_X((stage) + 1);                                                                                 \
@@ -248,7 +249,10 @@ __global__ __launch_bounds__(256, (w_sets<MT, NT>() == 2 ? 2 : 1)) void gemm_mfm
         }                                                                                                         \
     }
     const int mt_act = min(MT, (R - m0 + 31) >> 5);   // >= 1: m0 < R
-    if constexpr (MT == 4) {
+    if constexpr (MT == 6) {
+        if (mt_act == 6) SDLM_MAIN(6) else if (mt_act == 5) SDLM_MAIN(5) else if (mt_act == 4) SDLM_MAIN(4) else if (mt_act == 3) SDLM_MAIN(3)
+        else if (mt_act == 2) SDLM_MAIN(2) else SDLM_MAIN(1)
+    } else if constexpr (MT == 4) {
         if (mt_act == 4) SDLM_MAIN(4) else if (mt_act == 3) SDLM_MAIN(3) else if (mt_act == 2) SDLM_MAIN(2) else SDLM_MAIN(1)
     } else if constexpr (MT == 2) {
         if (mt_act == 2) SDLM_MAIN(2) else SDLM_MAIN(1)
@@ -463,6 +467,10 @@ static TileChoice choose(int epi, int rows, int min_rows, int N, int K, size_t s
     TileChoice c;
     c.MT = rows <= 32 ? 1 : rows <= 64 ? 2 : 4;
     c.NT = 2;
+    // Gate/up with 129..192 certain rows and enough column blocks for one workgroup on (nearly) every compute unit: one
+    // 192-row block per column block, so that no weight band is streamed by two workgroups.  (For the split-k
+    // projections the same tile was measured: it wants more splits, and the slab traffic costs more than it saves.)
+    if (epi == EPI_SWIGLU && min_rows > 128 && min_rows <= 192 && rows <= 384 && (N + 127) / 128 >= 192) c.MT = 6;
     if (epi != EPI_SWIGLU && epi != EPI_LMHEAD && c.MT < 4) {
         int mb = (rows + c.MT * 32 - 1) / (c.MT * 32);
         if ((long)((N + 255) / 256) * mb < 256) c.NT = 1;
@@ -504,7 +512,7 @@ static void launch_cfg(hipStream_t s, const TileChoice &c, MfmaArgs &a, int min_
     dim3 grid((first + 7) / 8 * 8 + (rest + 7) / 8 * 8), block(256);
 #define SDLM_GO(MT_, NT_) hipLaunchKernelGGL((gemm_mfma_k<MT_, NT_, EPI>), grid, block, 0, s, a)
     if (EPI == EPI_SWIGLU || EPI == EPI_LMHEAD || c.NT == 2) {
-        if (c.MT == 1) SDLM_GO(1, 2); else if (c.MT == 2) SDLM_GO(2, 2); else SDLM_GO(4, 2);
+        if (c.MT == 1) SDLM_GO(1, 2); else if (c.MT == 2) SDLM_GO(2, 2); else if (c.MT == 6 && EPI == EPI_SWIGLU) hipLaunchKernelGGL((gemm_mfma_k<(EPI == EPI_SWIGLU ? 6 : 4), 2, EPI>), grid, block, 0, s, a); else SDLM_GO(4, 2);
     } else {
         if (EPI == EPI_STORE_F32 || EPI == EPI_RESID) {
             if (c.MT == 1) hipLaunchKernelGGL((gemm_mfma_k<1, 1, (EPI == EPI_STORE_F32 || EPI == EPI_RESID) ? EPI : EPI_RESID>), grid, block, 0, s, a);

@@ -239,6 +239,7 @@ def mfma_cfg(**kw):
     ("g6-D4-batch1-long", dict(n_q_heads=12, n_kv_heads=2, hidden=384, ffn=1024), [700], 4, 0.6, False),
     ("g4-batch20-128-row-tiles", dict(n_q_heads=8, n_kv_heads=2, vocab=4096 + 160), [3 + 7 * i for i in range(20)], 4, 0.6, True),
     ("g5-D16", dict(n_q_heads=10, n_kv_heads=2, hidden=320, ffn=640, has_qkv_bias=False), [2, 50], 16, 0.3, True),
+    ("g4-batch36-192-row-gate-up-tile", dict(n_q_heads=8, n_kv_heads=2, hidden=256, ffn=24576), [3 + 2 * i for i in range(36)], 4, 0.6, True),
 ])
 def test_bf16_mfma_path(name, kw, lens, D, tau, paged):
     """The bf16 product path: MFMA GEMMs, MFMA block-masked attention (split KV), fused LM-head reduction."""
