@@ -488,7 +488,8 @@ static TileChoice choose(int epi, int rows, int min_rows, int N, int K, size_t s
             // tile is the more efficient one; the 128-wide tile takes over when the wide one would leave more
             // than a quarter of the units without work.
             const long ms = sure_blocks(rows, min_rows, c.MT), nb2 = (N + 255) / 256, nb1 = (N + 127) / 128;
-            const int sp2 = clamp(256 / (nb2 * ms));
+            int sp2 = clamp(256 / (nb2 * ms));
+            if (K <= 4096 && sp2 > 3) sp2 = 3;   // short k loops: beyond three splits the slabs' write + read-back costs more than the idle units
             if (nb2 * ms * sp2 >= 192) { c.NT = 2; c.splits = sp2; }
             else { c.NT = 1; c.splits = clamp(256 / (nb1 * ms)); }
         } else {
