@@ -576,7 +576,7 @@ int sdlm_decode_step(sdlm_ctx *c, int32_t *ids, int32_t *count, float *conf, flo
     auto launch_all = [&]() {
         const int rows = B * 2 * D;
         { Phase p(c, SDLM_PH_ROWS); launch_assemble_decode(s, c->st, c->rm, B, D, c->m.mask_token_id, c->L.group_rows, c->kg.staging_base, c->m.block_causal); }
-        run_layers(c, rows, B * ((2 * D + c->L.group_rows - 1) / c->L.group_rows), B * (D + 1));   // every sequence has >= 1 pending row
+        run_layers(c, rows, B * ((2 * D + c->L.group_rows - 1) / c->L.group_rows), B * (D + 1));   // >= 1 pending row per sequence (not on the first step after a prefill: the bound only shapes the launch)
         run_lm_head(c, B * D, logits);
         { Phase p(c, SDLM_PH_ACCEPT); launch_accept(s, c->st, c->ids_rows, c->conf_rows, B, D, c->r.tau, c->r.accept_rule, ids, count, conf); }
     };
