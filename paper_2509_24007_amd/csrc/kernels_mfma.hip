@@ -497,6 +497,12 @@ static TileChoice choose(int epi, int rows, int min_rows, int N, int K, size_t s
             c.splits = clamp((512 + wgs - 1) / wgs);
         }
     }
+    // every split must own at least one 64-deep slice: with ceil(S / splits) slices per split the last splits of an
+    // uneven division would be empty and their slabs never written
+    if (c.splits > 1) {
+        const int S = K / 64, per = (S + c.splits - 1) / c.splits;
+        c.splits = (S + per - 1) / per;
+    }
     return c;
 }
 

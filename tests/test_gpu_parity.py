@@ -480,3 +480,43 @@ def test_mfma_row_blocks_beyond_the_sure_ones():
     st, _ = lockstep(ctx, om, prompts, D, 0.6, steps, logit_tol=2e-2, conf_tol=1e-3, overrides=(ids, cnt), bf16=True, max_len=max_len)
     print("row blocks", st)
     ctx.close()
+
+
+# ------------------------------------------------------------------ seeded random shapes
+def _random_case(seed):
+    rng = np.random.RandomState(seed)
+    G = int(rng.choice([1, 2, 3, 4, 7, 8]))
+    Hk = int(rng.choice([1, 2, 3]))
+    hidden = int(rng.choice([128, 192, 256, 320, 448]))
+    ffn = int(rng.choice([192, 320, 576, 1088]))
+    vocab = int(rng.choice([515, 1000, 2048, 3001]))
+    D = int(rng.choice([1, 2, 3, 4, 5, 8]))
+    B = int(rng.choice([1, 3, 9, 17, 30]))
+    lens = [int(v) for v in rng.randint(1, 70, size=B)]
+    paged = bool(rng.randint(0, 2))
+    kw = dict(n_q_heads=G * Hk, n_kv_heads=Hk, hidden=hidden, ffn=ffn, vocab=vocab, has_qkv_bias=bool(rng.randint(0, 2)),
+              block_causal=bool(rng.randint(0, 4) == 0))
+    return kw, lens, D, paged
+
+
+@pytest.mark.parametrize("seed", list(range(24)))
+def test_bf16_mfma_random_shapes(seed):
+    """Seeded random model shapes, batch sizes, block sizes and layouts through the matrix-core path: every tile
+    policy branch (row-tile height, column-tile width, split counts, ragged and possibly-empty row blocks) sees shapes
+    it was not tuned on."""
+    kw, lens, D, paged = _random_case(seed)
+    m = mfma_cfg(**kw)
+    om, g_dev, layers_dev = both_models(m, seed=100 + seed, std=0.05)
+    prompts = [syn.uniform_int(seed, f"rs{i}", n, 0, m.vocab - 1).numpy() for i, n in enumerate(lens)]
+    steps = 4
+    ovr = syn.make_overrides(200 + seed, steps, len(lens), D, m.vocab)
+    max_len = max(lens) + steps * D + D
+    n_pages = sum((n + steps * D + 15) // 16 + 1 for n in lens)
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=len(lens), max_seq_len=max_len, D=D, tau=0.5, paged=paged, n_pages=n_pages,
+                      prefill_rows=int(np.random.RandomState(seed).choice([32, 64, 200])))
+    assert ctx.kernel_info == "mfma-bf16"
+    verify = 0 if (2 <= D <= 5 and seed % 2 == 0) else None
+    st, _ = lockstep(ctx, om, prompts, D, 0.5, steps, logit_tol=2e-2, conf_tol=1e-3, overrides=ovr, bf16=True, max_len=max_len,
+                     verify_rule=verify)
+    print(f"random shape {seed}: {kw} B={len(lens)} D={D} paged={paged} verify={verify}", st)
+    ctx.close()
