@@ -520,3 +520,55 @@ def test_bf16_mfma_random_shapes(seed):
                      verify_rule=verify)
     print(f"random shape {seed}: {kw} B={len(lens)} D={D} paged={paged} verify={verify}", st)
     ctx.close()
+
+
+@pytest.mark.parametrize("seed", list(range(12)))
+def test_fp32_generic_random_shapes(seed):
+    """The same for the generic kernels (fp32 debug mode): head sizes 32..128, sizes that are not multiples of any
+    tile, exact ids and gamma."""
+    rng = np.random.RandomState(1000 + seed)
+    Hk = int(rng.choice([1, 2, 3]))
+    G = int(rng.choice([1, 2, 4, 5]))
+    d = int(rng.choice([32, 64, 96, 128]))
+    m = gpu_cfg(n_q_heads=G * Hk, n_kv_heads=Hk, head_dim=d, hidden=int(rng.choice([36, 64, 100, 132])),
+                ffn=int(rng.choice([40, 112, 250])), vocab=int(rng.choice([97, 300, 1001])),
+                has_qkv_bias=bool(rng.randint(0, 2)), block_causal=bool(rng.randint(0, 4) == 0))
+    D = int(rng.choice([1, 2, 3, 4, 6, 9]))
+    B = int(rng.choice([1, 2, 5, 11]))
+    lens = [int(v) for v in rng.randint(1, 50, size=B)]
+    paged = bool(rng.randint(0, 2))
+    om, g_dev, layers_dev = both_models(m, seed=300 + seed, std=0.3)
+    prompts = [syn.uniform_int(seed, f"rf{i}", n, 0, m.vocab - 1).numpy() for i, n in enumerate(lens)]
+    steps = 4
+    ovr = syn.make_overrides(400 + seed, steps, B, D, m.vocab)
+    max_len = max(lens) + steps * D + D
+    n_pages = sum((n + steps * D + 15) // 16 + 1 for n in lens)
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=B, max_seq_len=max_len, D=D, tau=0.5, paged=paged, n_pages=n_pages,
+                      prefill_rows=int(rng.choice([16, 64, 200])))
+    verify = int(rng.randint(0, 2)) if 2 <= D <= 9 and seed % 2 == 0 else None
+    st, _ = lockstep(ctx, om, prompts, D, 0.5, steps, logit_tol=1e-4, conf_tol=1e-5, overrides=ovr, max_len=max_len, verify_rule=verify)
+    print(f"random fp32 shape {seed}: B={B} D={D} d={d} paged={paged} verify={verify}", st)
+    assert st.id_near_tie == 0
+    ctx.close()
+
+
+@pytest.mark.parametrize("seed", list(range(6)))
+def test_bf16_mfma_random_long_contexts(seed):
+    """Few sequences with contexts of a few hundred tokens: the KV chunking policy (chunk size halves until there are
+    enough work items) and the merge of many chunks see lengths on both sides of every chunk boundary."""
+    rng = np.random.RandomState(2000 + seed)
+    G = int(rng.choice([1, 4, 7, 16]))
+    m = mfma_cfg(n_q_heads=G * 2, n_kv_heads=2, hidden=int(rng.choice([128, 256])), ffn=256, vocab=1000)
+    D = int(rng.choice([2, 4, 8]))
+    B = int(rng.choice([1, 2, 3]))
+    lens = [int(v) for v in rng.randint(100, 520, size=B)]
+    om, g_dev, layers_dev = both_models(m, seed=500 + seed, std=0.05)
+    prompts = [syn.uniform_int(seed, f"rl{i}", n, 0, m.vocab - 1).numpy() for i, n in enumerate(lens)]
+    steps = 3
+    max_len = max(lens) + steps * D + D
+    paged = bool(rng.randint(0, 2))
+    n_pages = sum((n + steps * D + 15) // 16 + 1 for n in lens)
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=B, max_seq_len=max_len, D=D, tau=0.5, paged=paged, n_pages=n_pages, prefill_rows=128)
+    st, _ = lockstep(ctx, om, prompts, D, 0.5, steps, logit_tol=2e-2, conf_tol=1e-3, bf16=True, max_len=max_len)
+    print(f"random long {seed}: G={G} B={B} D={D} lens={lens} paged={paged}", st)
+    ctx.close()
