@@ -212,6 +212,15 @@ int sdlm_debug_rows(sdlm_ctx *ctx, int32_t *tok, int32_t *pos, int32_t *seq, int
 int sdlm_debug_read_kv(sdlm_ctx *ctx, int32_t layer, int32_t seq, int32_t kv_head, int32_t pos0, int32_t count,
                        float *k_out, float *v_out);
 
+/*
+ * Host logic only (no GPU work): the launch shape the bf16 matrix-core GEMM takes for `rows` launch rows of which
+ * `min_rows` certainly exist (0: unknown), an [n, k] weight matrix (k a multiple of 64) and an epilogue (0: plain fp32
+ * store, 1: residual add, 2: SiLU(gate)*up, 3: LM head).  Outputs: rows and columns of a workgroup's tile and the
+ * number of splits along k.  For tests of the tile policy.  Errors: SDLM_EINVAL.
+ */
+int sdlm_debug_gemm_plan(int32_t epilogue, int32_t rows, int32_t min_rows, int32_t n, int32_t k, int32_t *tile_rows, int32_t *tile_cols,
+                         int32_t *splits);
+
 /* Rows the activation buffers are sized for (decode: batch * 2D; prefill pass size). */
 int32_t sdlm_max_rows(const sdlm_ctx *ctx);
 

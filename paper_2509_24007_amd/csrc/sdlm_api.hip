@@ -719,6 +719,16 @@ int sdlm_debug_read_kv(sdlm_ctx *c, int32_t layer, int32_t seq, int32_t kv_head,
     return SDLM_OK;
 }
 
+int sdlm_debug_gemm_plan(int32_t epilogue, int32_t rows, int32_t min_rows, int32_t n, int32_t k, int32_t *tile_rows, int32_t *tile_cols,
+                         int32_t *splits)
+{
+    if (!tile_rows || !tile_cols || !splits || rows < 1 || n < 1 || k < 64 || k % 64 || epilogue < 0 || epilogue > 3) return SDLM_EINVAL;
+    int mt, nt, sp;
+    mfma_gemm_plan(epilogue == 3 ? 4 : epilogue, rows, min_rows, n, k, (size_t)16 << 20, &mt, &nt, &sp);
+    *tile_rows = 32 * mt; *tile_cols = 128 * nt; *splits = sp;
+    return SDLM_OK;
+}
+
 int32_t sdlm_max_rows(const sdlm_ctx *c) { return c ? c->L.max_rows : 0; }
 
 int sdlm_profile(sdlm_ctx *c, int32_t enable)

@@ -20,7 +20,7 @@ OK, EINVAL, ECAPACITY, ESTATE, EHIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("sdlm_workspace_bytes", "sdlm_create", "sdlm_init_weights", "sdlm_prefill", "sdlm_decode_step",
            "sdlm_graph", "sdlm_verify_step", "sdlm_kv_commit", "sdlm_get_lengths", "sdlm_debug_tap", "sdlm_debug_rows", "sdlm_debug_read_kv",
-           "sdlm_max_rows", "sdlm_profile", "sdlm_profile_read", "sdlm_kernel_info", "sdlm_last_error",
+           "sdlm_debug_gemm_plan", "sdlm_max_rows", "sdlm_profile", "sdlm_profile_read", "sdlm_kernel_info", "sdlm_last_error",
            "sdlm_destroy")
 
 
@@ -70,6 +70,8 @@ def load():
     L.sdlm_prefill.argtypes = [vp, i32, vp, vp]
     L.sdlm_decode_step.restype = C.c_int
     L.sdlm_decode_step.argtypes = [vp, vp, vp, vp, vp]
+    L.sdlm_debug_gemm_plan.restype = C.c_int
+    L.sdlm_debug_gemm_plan.argtypes = [C.c_int32] * 5 + [vp, vp, vp]
     L.sdlm_graph.restype = C.c_int
     L.sdlm_graph.argtypes = [vp, C.c_int32]
     L.sdlm_verify_step.restype = C.c_int
@@ -111,6 +113,15 @@ def model_cfg(m) -> ModelCfg:
     return ModelCfg(m.n_layers, m.hidden, m.n_q_heads, m.n_kv_heads, m.head_dim, m.ffn, m.vocab,
                     m.rope_theta, m.rms_eps, m.logit_scale, 0 if m.dtype == "fp32" else 1, m.mask_token_id,
                     int(bool(m.has_qkv_bias)), int(bool(getattr(m, "block_causal", False))))
+
+
+def gemm_plan(epilogue: int, rows: int, min_rows: int, n: int, k: int):
+    """(tile rows, tile columns, k splits) of the matrix-core GEMM launch for this problem; host logic, no GPU needed."""
+    tr, tc, sp = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+    rc = load().sdlm_debug_gemm_plan(epilogue, rows, min_rows, n, k, C.byref(tr), C.byref(tc), C.byref(sp))
+    if rc != 0:
+        raise SdlmError(rc, "bad arguments to sdlm_debug_gemm_plan")
+    return tr.value, tc.value, sp.value
 
 
 def _dp(t: Optional[torch.Tensor]):
