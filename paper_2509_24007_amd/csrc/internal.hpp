@@ -109,7 +109,7 @@ void launch_verify_accept(hipStream_t s, const SeqState &st, const int32_t *ids_
                           int32_t *ids_out, int32_t *count_out);
 void launch_embed(hipStream_t s, int dtype, float *x, const void *E, const RowMeta &rm, int max_rows, int h, int V);
 void launch_rmsnorm(hipStream_t s, int dtype, void *out, float *x, const void *g, int h, float eps, const int32_t *row_index,
-                    const int32_t *p_count, int max_rows, const float *slabs, int n_slabs, size_t slab_stride);
+                    const int32_t *p_count, int max_rows, int min_rows, const float *slabs, int n_slabs, size_t slab_stride);   // min_rows: rows that certainly exist
 void launch_gemm_generic(hipStream_t s, int dtype, int epi, const GemmArgs &a);
 void launch_rope_scatter(hipStream_t s, int dtype, const float *qkv, int n_slabs, size_t slab_stride, void *q_out, void *pool_layer,
                          const KvGeom &kg, const RowMeta &rm, const SeqState &st, const float2 *rope, int n_q_heads, int max_rows);

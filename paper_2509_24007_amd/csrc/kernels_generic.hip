@@ -170,20 +170,28 @@ __device__ inline float block_sum(float v, float *red)
 // A row lives in registers between the two passes (NV float4 per thread, h <= 1024 NV).
 template <typename T, int NV>
 __global__ __launch_bounds__(256) void rmsnorm_k(T *out, float *x, const T *g, int h, float eps, const int32_t *row_index,
-                                                 const int32_t *p_count, const float *slabs, int n_slabs, size_t slab_stride)
+                                                 const int32_t *p_count, int sure, const float *slabs, int n_slabs, size_t slab_stride)
 {
     __shared__ float red[4];
     const int j = blockIdx.x;
-    if (j >= *p_count) return;
+    if (j >= sure && j >= *p_count) return;   // the first `sure` rows exist for certain: no wait for the device count
     const int row = row_index ? row_index[j] : j;
     float *xr = x + (size_t)row * h;
-    float4 v[NV];
+    float4 v[NV], gv[NV];   // the gains are requested together with the row, not after the reduction
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
         const int k = (i * 256 + threadIdx.x) * 4;
         v[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+        gv[i] = v[i];
         if (k < h) {
             v[i] = *(const float4 *)(xr + k);
+            if constexpr (sizeof(T) == 2) {
+                const uint2 u = *(const uint2 *)(g + k);
+                gv[i] = make_float4(bf16_to_f((bf16_t)(u.x & 0xffff)), bf16_to_f((bf16_t)(u.x >> 16)),
+                                    bf16_to_f((bf16_t)(u.y & 0xffff)), bf16_to_f((bf16_t)(u.y >> 16)));
+            } else {
+                gv[i] = *(const float4 *)(g + k);
+            }
             for (int sl = 0; sl < n_slabs; ++sl) {
                 float4 p = *(const float4 *)(slabs + sl * slab_stride + (size_t)row * h + k);
                 v[i].x += p.x; v[i].y += p.y; v[i].z += p.z; v[i].w += p.w;
@@ -203,8 +211,8 @@ __global__ __launch_bounds__(256) void rmsnorm_k(T *out, float *x, const T *g, i
     for (int i = 0; i < NV; ++i) {
         const int k = (i * 256 + threadIdx.x) * 4;
         if (k >= h) continue;
-        const float o0 = v[i].x * inv * to_f<T>(g[k]), o1 = v[i].y * inv * to_f<T>(g[k + 1]);
-        const float o2 = v[i].z * inv * to_f<T>(g[k + 2]), o3 = v[i].w * inv * to_f<T>(g[k + 3]);
+        const float o0 = v[i].x * inv * gv[i].x, o1 = v[i].y * inv * gv[i].y;
+        const float o2 = v[i].z * inv * gv[i].z, o3 = v[i].w * inv * gv[i].w;
         T *dst = out + (size_t)j * h + k;
         if constexpr (sizeof(T) == 2) {
             *(uint2 *)dst = make_uint2((uint32_t)f_to_bf16(o0) | ((uint32_t)f_to_bf16(o1) << 16),
@@ -217,18 +225,18 @@ __global__ __launch_bounds__(256) void rmsnorm_k(T *out, float *x, const T *g, i
 
 template <typename T>
 static void rmsnorm_t(hipStream_t s, void *out, float *x, const void *g, int h, float eps, const int32_t *row_index,
-                      const int32_t *p_count, int max_rows, const float *slabs, int n_slabs, size_t slab_stride)
+                      const int32_t *p_count, int max_rows, int min_rows, const float *slabs, int n_slabs, size_t slab_stride)
 {
-#define SDLM_RMS(NV) hipLaunchKernelGGL((rmsnorm_k<T, NV>), dim3(max_rows), dim3(256), 0, s, (T *)out, x, (const T *)g, h, eps, row_index, p_count, slabs, n_slabs, slab_stride)
+#define SDLM_RMS(NV) hipLaunchKernelGGL((rmsnorm_k<T, NV>), dim3(max_rows), dim3(256), 0, s, (T *)out, x, (const T *)g, h, eps, row_index, p_count, min_rows, slabs, n_slabs, slab_stride)
     if (h <= 2048) SDLM_RMS(2); else if (h <= 4096) SDLM_RMS(4); else if (h <= 8192) SDLM_RMS(8); else SDLM_RMS(16);
 #undef SDLM_RMS
 }
 
 void launch_rmsnorm(hipStream_t s, int dtype, void *out, float *x, const void *g, int h, float eps, const int32_t *row_index,
-                    const int32_t *p_count, int max_rows, const float *slabs, int n_slabs, size_t slab_stride)
+                    const int32_t *p_count, int max_rows, int min_rows, const float *slabs, int n_slabs, size_t slab_stride)
 {
-    if (dtype == 0) rmsnorm_t<float>(s, out, x, g, h, eps, row_index, p_count, max_rows, slabs, n_slabs, slab_stride);
-    else rmsnorm_t<bf16_t>(s, out, x, g, h, eps, row_index, p_count, max_rows, slabs, n_slabs, slab_stride);
+    if (dtype == 0) rmsnorm_t<float>(s, out, x, g, h, eps, row_index, p_count, max_rows, min_rows, slabs, n_slabs, slab_stride);
+    else rmsnorm_t<bf16_t>(s, out, x, g, h, eps, row_index, p_count, max_rows, min_rows, slabs, n_slabs, slab_stride);
 }
 
 // ------------------------------------------------------------------------------------------------ GEMM (FMA)

@@ -154,6 +154,7 @@ struct sdlm_ctx {
     int pend_slabs = 0;                  // split-k slabs of the last residual projection not yet added to x
     size_t pend_stride = 0;
     bool prefilled = false, stepped = false;
+    bool committed = false;              // a commit has happened since the prefill: every sequence has >= 1 pending row
     std::vector<int32_t> n_ub;           // host upper bound of n_b
     std::vector<Tap> taps;
     // graph replay of the decode step (opt-in): the launch sequence of a step is fixed once the batch is, all sizes
@@ -233,7 +234,7 @@ void run_layers(sdlm_ctx *c, int rows, int groups, int rows_sure)
         const LayerW &w = c->lw[l];
         char *pool_l = c->pool + (size_t)l * c->kg.layer_stride * e;
         run_taps(c, l, 0, c->x, (size_t)rows * h * 4);
-        { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xn, c->x, w.attn_norm, h, m.rms_eps, nullptr, c->rm.counts, rows, c->slabs, c->pend_slabs, c->pend_stride); c->pend_slabs = 0; }
+        { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xn, c->x, w.attn_norm, h, m.rms_eps, nullptr, c->rm.counts, rows, rows_sure, c->slabs, c->pend_slabs, c->pend_stride); c->pend_slabs = 0; }
         int qkv_slabs = 1;
         {
             Phase p(c, SDLM_PH_QKV);
@@ -266,7 +267,7 @@ void run_layers(sdlm_ctx *c, int rows, int groups, int rows_sure)
             } else launch_gemm_generic(s, dt, EPI_RESID, a);
         }
         run_taps(c, l, 6, c->x, (size_t)rows * h * 4);
-        { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xn, c->x, w.ffn_norm, h, m.rms_eps, nullptr, c->rm.counts, rows, c->slabs, c->pend_slabs, c->pend_stride); c->pend_slabs = 0; }
+        { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xn, c->x, w.ffn_norm, h, m.rms_eps, nullptr, c->rm.counts, rows, rows_sure, c->slabs, c->pend_slabs, c->pend_stride); c->pend_slabs = 0; }
         {
             Phase p(c, SDLM_PH_GATEUP);
             GemmArgs a{c->xn, w.w_gate, w.w_up, nullptr, nullptr, c->act, c->rm.counts, rows, F, h, 1.f, rows_sure};
@@ -291,7 +292,7 @@ void run_lm_head(sdlm_ctx *c, int lm_rows, float *logits)
 {
     hipStream_t s = c->stream;
     const int dt = c->m.dtype, h = c->m.hidden, V = c->m.vocab;
-    { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xhat, c->x, c->final_norm, h, c->m.rms_eps, c->rm.blk_row, c->rm.counts + 2, lm_rows, c->slabs, c->pend_slabs, c->pend_stride); c->pend_slabs = 0; }
+    { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xhat, c->x, c->final_norm, h, c->m.rms_eps, c->rm.blk_row, c->rm.counts + 2, lm_rows, lm_rows, c->slabs, c->pend_slabs, c->pend_stride); c->pend_slabs = 0; }
     run_taps(c, 0, 4, c->xhat, (size_t)lm_rows * h * c->L.esz);
     {
         Phase p(c, SDLM_PH_LMHEAD);
@@ -485,7 +486,7 @@ int sdlm_prefill(sdlm_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
     if (c->r.kv_layout == 1 && pages_needed > c->L.n_pages)
         return fail(c, SDLM_ECAPACITY, "prompts need %ld pages, the pool has %d", pages_needed, c->L.n_pages);
     c->batch = batch;
-    c->prefilled = false; c->stepped = false;
+    c->prefilled = false; c->stepped = false; c->committed = false;
     drop_graph(c);   // the batch size is baked into the captured launches
     // sequence state
     const int B = c->r.max_batch;
@@ -576,7 +577,7 @@ int sdlm_decode_step(sdlm_ctx *c, int32_t *ids, int32_t *count, float *conf, flo
     auto launch_all = [&]() {
         const int rows = B * 2 * D;
         { Phase p(c, SDLM_PH_ROWS); launch_assemble_decode(s, c->st, c->rm, B, D, c->m.mask_token_id, c->L.group_rows, c->kg.staging_base, c->m.block_causal); }
-        run_layers(c, rows, B * ((2 * D + c->L.group_rows - 1) / c->L.group_rows), B * (D + 1));   // >= 1 pending row per sequence (not on the first step after a prefill: the bound only shapes the launch)
+        run_layers(c, rows, B * ((2 * D + c->L.group_rows - 1) / c->L.group_rows), B * (D + (c->committed ? 1 : 0)));   // after a commit every sequence has >= 1 pending row
         run_lm_head(c, B * D, logits);
         { Phase p(c, SDLM_PH_ACCEPT); launch_accept(s, c->st, c->ids_rows, c->conf_rows, B, D, c->r.tau, c->r.accept_rule, ids, count, conf); }
     };
@@ -655,6 +656,7 @@ int sdlm_kv_commit(sdlm_ctx *c, const int32_t *ids_override, const int32_t *coun
     HIPCHK(c, hipGetLastError());
     for (int b = 0; b < B; ++b) c->n_ub[b] += D;
     c->stepped = false;
+    if (!c->committed) { c->committed = true; drop_graph(c); }   // the certain-row bound of the step's launches changes
     return SDLM_OK;
 }
 
