@@ -112,7 +112,7 @@ void launch_rmsnorm(hipStream_t s, int dtype, void *out, float *x, const void *g
                     const int32_t *p_count, int max_rows, int min_rows, const float *slabs, int n_slabs, size_t slab_stride);   // min_rows: rows that certainly exist
 void launch_gemm_generic(hipStream_t s, int dtype, int epi, const GemmArgs &a);
 void launch_rope_scatter(hipStream_t s, int dtype, const float *qkv, int n_slabs, size_t slab_stride, void *q_out, void *pool_layer,
-                         const KvGeom &kg, const RowMeta &rm, const SeqState &st, const float2 *rope, int n_q_heads, int max_rows);
+                         const KvGeom &kg, const RowMeta &rm, const SeqState &st, const float2 *rope, int n_q_heads, int max_rows, int min_rows);
 void launch_attn_generic(hipStream_t s, int dtype, const void *q, void *out, const void *pool_layer, const KvGeom &kg,
                          const RowMeta &rm, const SeqState &st, int n_q_heads, int max_rows);
 void launch_lm_reduce(hipStream_t s, const float *logits, int V, int32_t *ids, float *conf, int conf_fn,

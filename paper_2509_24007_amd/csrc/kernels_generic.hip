@@ -319,12 +319,12 @@ void launch_gemm_generic(hipStream_t s, int dtype, int epi, const GemmArgs &a)
 // grid (rows, ceil((Hq + 2 Hkv) / 4)): one wavefront per (row, head), lane i < d/2 owns the pair (i, i + d/2).
 template <typename T>
 __global__ __launch_bounds__(256) void rope_scatter_k(const float *qkv, int n_slabs, size_t slab_stride, T *q_out, T *pool, KvGeom kg,
-                                                      RowMeta rm, SeqState st, const float2 *rope, int Hq)
+                                                      RowMeta rm, SeqState st, const float2 *rope, int Hq, int sure)
 {
     const int r = blockIdx.x;
     const int d = kg.head_dim, half = d >> 1, Hk = kg.n_kv_heads, nq = Hq * d, nk = Hk * d;
     const int head = blockIdx.y * 4 + (threadIdx.x >> 6), i = threadIdx.x & 63;   // heads: Hq of q, then Hkv of k, then Hkv of v
-    if (head >= Hq + 2 * Hk || i >= half || r >= rm.counts[0]) return;
+    if (head >= Hq + 2 * Hk || i >= half || (r >= sure && r >= rm.counts[0])) return;   // certain rows: no wait for the count
     const float *src = qkv + (size_t)r * (nq + 2 * nk) + head * d + i;
     float x0 = src[0], x1 = src[half];
     for (int sl = 1; sl < n_slabs; ++sl) { x0 += src[sl * slab_stride]; x1 += src[sl * slab_stride + half]; }
@@ -355,11 +355,11 @@ __global__ __launch_bounds__(256) void rope_scatter_k(const float *qkv, int n_sl
 }
 
 void launch_rope_scatter(hipStream_t s, int dtype, const float *qkv, int n_slabs, size_t slab_stride, void *q_out, void *pool_layer,
-                         const KvGeom &kg, const RowMeta &rm, const SeqState &st, const float2 *rope, int n_q_heads, int max_rows)
+                         const KvGeom &kg, const RowMeta &rm, const SeqState &st, const float2 *rope, int n_q_heads, int max_rows, int min_rows)
 {
     dim3 grid(max_rows, (n_q_heads + 2 * kg.n_kv_heads + 3) / 4);
-    if (dtype == 0) hipLaunchKernelGGL(rope_scatter_k<float>, grid, dim3(256), 0, s, qkv, n_slabs, slab_stride, (float *)q_out, (float *)pool_layer, kg, rm, st, rope, n_q_heads);
-    else hipLaunchKernelGGL(rope_scatter_k<bf16_t>, grid, dim3(256), 0, s, qkv, n_slabs, slab_stride, (bf16_t *)q_out, (bf16_t *)pool_layer, kg, rm, st, rope, n_q_heads);
+    if (dtype == 0) hipLaunchKernelGGL(rope_scatter_k<float>, grid, dim3(256), 0, s, qkv, n_slabs, slab_stride, (float *)q_out, (float *)pool_layer, kg, rm, st, rope, n_q_heads, min_rows);
+    else hipLaunchKernelGGL(rope_scatter_k<bf16_t>, grid, dim3(256), 0, s, qkv, n_slabs, slab_stride, (bf16_t *)q_out, (bf16_t *)pool_layer, kg, rm, st, rope, n_q_heads, min_rows);
 }
 
 // ------------------------------------------------------------------------------------------------ attention

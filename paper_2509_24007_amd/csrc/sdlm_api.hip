@@ -243,7 +243,7 @@ void run_layers(sdlm_ctx *c, int rows, int groups, int rows_sure)
         }
         {
             Phase p(c, SDLM_PH_ROPE);
-            launch_rope_scatter(s, dt, qkv_slabs > 1 ? c->slabs : c->qkv, qkv_slabs, (size_t)rows * nqkv, c->q, pool_l, c->kg, c->rm, c->st, c->rope, m.n_q_heads, rows);
+            launch_rope_scatter(s, dt, qkv_slabs > 1 ? c->slabs : c->qkv, qkv_slabs, (size_t)rows * nqkv, c->q, pool_l, c->kg, c->rm, c->st, c->rope, m.n_q_heads, rows, rows_sure);
         }
         run_taps(c, l, 5, c->q, (size_t)rows * nq * e);
         bool merge = false;
