@@ -10,6 +10,7 @@ Prints ONE JSON line: metric = accepted tokens/s over the timed steps, plus bloc
 object of the dominant kernel (HIP-event timed inside the timed region) and the CPU oracle baseline.
 """
 import argparse
+import dataclasses
 import json
 import os
 import sys
@@ -50,6 +51,9 @@ def parse():
                     help="phases bracketed by HIP events inside the timed region: one phase name (default: the dominant kernel), "
                          "main (all six big kernels, ~6%% slower steps) or none; the per-kernel table of the other phases comes "
                          "from up to 32 extra untimed steps")
+    ap.add_argument("--conf-fn", type=int, default=0, choices=(0, 1), help="0: softmax probability of the arg-max token; 1: entropy-normalised confidence")
+    ap.add_argument("--accept-rule", type=int, default=0, choices=(0, 1), help="0: cumulative product >= tau (the paper's rule); 1: every leading confidence >= tau")
+    ap.add_argument("--block-causal", action="store_true", help="the causal-in-block ablation instead of mutual attention inside the block")
     ap.add_argument("--prefill-rows", type=int, default=0, help="rows per prefill pass (0: library default)")
     ap.add_argument("--verify", type=int, default=None, choices=(0, 1),
                     help="self-speculative decoding: every step is followed by the verification pass and commits gamma_verify "
@@ -167,6 +171,8 @@ def main():
 
     wl = syn.workloads()[a.config]
     m, r = wl.model, wl.run
+    if a.block_causal:
+        m = dataclasses.replace(m, block_causal=True)
     tau = a.tau if a.tau is not None else r.tau
     taus = [tau] + ([t for t in (r.taus or []) if t != tau] if a.sweep else [])
     B, D = r.batch, r.block_D
@@ -178,7 +184,7 @@ def main():
     side = torch.cuda.Stream() if a.graph else None
     with torch.cuda.stream(side):
         ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=B, max_seq_len=max_len, block_D=D, tau=tau, paged=r.paged,
-                           n_pages=n_pages, prefill_rows=a.prefill_rows)
+                           n_pages=n_pages, prefill_rows=a.prefill_rows, conf_fn=a.conf_fn, accept_rule=a.accept_rule)
     torch.cuda.synchronize()
     if a.graph:
         ctx.graph(True)
@@ -196,7 +202,7 @@ def main():
             ctx.close()
             with torch.cuda.stream(side):
                 ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=B, max_seq_len=max_len, block_D=D, tau=tv, paged=r.paged, n_pages=n_pages,
-                                   prefill_rows=a.prefill_rows)
+                                   prefill_rows=a.prefill_rows, conf_fn=a.conf_fn, accept_rule=a.accept_rule)
             torch.cuda.synchronize()
             if a.graph:
                 ctx.graph(True)
@@ -278,6 +284,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": wl.name, "batch": B, "block_D": D, "tau": main_r["tau"], "paged_kv": bool(r.paged),
                    "prompt_len": [r.prompt_lo, r.prompt_hi], "kernels": ctx.kernel_info, "graph_replay": bool(a.graph),
+                   "conf_fn": a.conf_fn, "accept_rule": a.accept_rule, "block_causal": bool(a.block_causal),
                    "decoding": "greedy longest-prefix (gamma_tau)" if a.verify is None else
                                "self-speculative (gamma_verify, rule %d): a step is the block step plus the verification pass" % a.verify},
         "gamma_hist": main_r["hist"],
