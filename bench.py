@@ -54,6 +54,10 @@ def parse():
     ap.add_argument("--conf-fn", type=int, default=0, choices=(0, 1), help="0: softmax probability of the arg-max token; 1: entropy-normalised confidence")
     ap.add_argument("--accept-rule", type=int, default=0, choices=(0, 1), help="0: cumulative product >= tau (the paper's rule); 1: every leading confidence >= tau")
     ap.add_argument("--block-causal", action="store_true", help="the causal-in-block ablation instead of mutual attention inside the block")
+    ap.add_argument("--force-accept", type=int, default=0,
+                    help="commit this many of the step's tokens for every sequence instead of gamma (random weights accept about "
+                         "1.05 tokens/step; this shows the step at a trained model's acceptance, e.g. 2). The reported rate "
+                         "is then tokens committed/s, labelled as forced")
     ap.add_argument("--prefill-rows", type=int, default=0, help="rows per prefill pass (0: library default)")
     ap.add_argument("--verify", type=int, default=None, choices=(0, 1),
                     help="self-speculative decoding: every step is followed by the verification pass and commits gamma_verify "
@@ -96,7 +100,7 @@ def algorithmic_bytes(m, esz, lens_sum, R):
     return weights, kv
 
 
-def run_tau(ctx, m, r, prompts, tau_idx, steps, warmup, prof_phases, table_steps=0, verify=None):
+def run_tau(ctx, m, r, prompts, tau_idx, steps, warmup, prof_phases, table_steps=0, verify=None, force=0):
     """Warm-up, then the timed region (only `prof_phases` carry events: every bracketed phase costs two event records
     per launch), then `table_steps` untimed extra steps with every main phase bracketed for the per-kernel table."""
     import torch
@@ -108,11 +112,17 @@ def run_tau(ctx, m, r, prompts, tau_idx, steps, warmup, prof_phases, table_steps
     run_tau.prefill_s = time.perf_counter() - tp
     ids = torch.zeros(warmup + steps + table_steps, B, D, dtype=torch.int32, device="cuda")
     cnt = torch.zeros(warmup + steps + table_steps, B, dtype=torch.int32, device="cuda")
+    forced = torch.full((B,), force, dtype=torch.int32, device="cuda") if force else None
+    torch.cuda.synchronize()
+
     def one(t):
         ctx.decode_step(ids[t], cnt[t])
         if verify is not None:
             ctx.verify_step(verify, None, cnt[t])      # the committed count becomes gamma_verify
-        ctx.kv_commit()
+        if forced is not None:
+            ctx.kv_commit(ids[t], forced)
+        else:
+            ctx.kv_commit()
     for t in range(warmup):
         one(t)
     torch.cuda.synchronize()
@@ -208,8 +218,10 @@ def main():
                 ctx.graph(True)
             build_model(ctx, m, wl.seed)
         t0 = time.perf_counter()
-        dt, cnt, phases, n_end, tphases = run_tau(ctx, m, r, prompts, ti, a.steps, a.warmup, prof, table_steps if ti == 0 else 0, a.verify)
+        dt, cnt, phases, n_end, tphases = run_tau(ctx, m, r, prompts, ti, a.steps, a.warmup, prof, table_steps if ti == 0 else 0, a.verify, a.force_accept)
         t_total = time.perf_counter() - t0
+        if a.force_accept:
+            cnt = torch.full_like(cnt, a.force_accept)
         timed = cnt[a.warmup:a.warmup + a.steps].numpy().astype(np.int64)
         accepted = int(timed.sum())
         hist = np.bincount(timed.ravel(), minlength=D + 1)[1:].tolist()
@@ -285,6 +297,7 @@ def main():
         "config": {"workload": wl.name, "batch": B, "block_D": D, "tau": main_r["tau"], "paged_kv": bool(r.paged),
                    "prompt_len": [r.prompt_lo, r.prompt_hi], "kernels": ctx.kernel_info, "graph_replay": bool(a.graph),
                    "conf_fn": a.conf_fn, "accept_rule": a.accept_rule, "block_causal": bool(a.block_causal),
+                   **({"forced_accept_per_step": a.force_accept} if a.force_accept else {}),
                    "decoding": "greedy longest-prefix (gamma_tau)" if a.verify is None else
                                "self-speculative (gamma_verify, rule %d): a step is the block step plus the verification pass" % a.verify},
         "gamma_hist": main_r["hist"],
