@@ -127,11 +127,16 @@ def run_tau(ctx, m, r, prompts, tau_idx, steps, warmup, prof_phases, table_steps
         one(t)
     torch.cuda.synchronize()
     ctx.profile(prof_phases)
+    # one event per step on the library's stream: the spread of the step's device time (median, p10, p90)
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t0 = time.perf_counter()
+    marks[0].record(ctx.stream)
     for t in range(warmup, warmup + steps):
         one(t)
+        marks[t - warmup + 1].record(ctx.stream)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    run_tau.step_ms = [marks[i].elapsed_time(marks[i + 1]) for i in range(steps)]
     phases = ctx.profile_read()
     table = {}
     if table_steps:
@@ -143,6 +148,26 @@ def run_tau(ctx, m, r, prompts, tau_idx, steps, warmup, prof_phases, table_steps
     ctx.profile(None)
     n, c = ctx.get_lengths()
     return t1 - t0, cnt.cpu(), phases, n, table
+
+
+def copy_ceiling(nbytes=1 << 30, reps=8):
+    """A plain device-to-device copy (torch's copy kernel), the streaming rate this card reaches in practice: bytes read
+    plus bytes written over the mean duration of `reps` copies."""
+    import torch
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    del src, dst
+    torch.cuda.empty_cache()
+    return {"GBs": 2 * nbytes / (ms * 1e-3) / 1e9, "copy_bytes": nbytes, "reps": reps,
+            "kind": "device-to-device copy of one buffer, read + written bytes over the mean copy time"}
 
 
 def cpu_baseline(m, host_g, host_layers, prompt, D, tau, budget_s=12.0, max_steps=64, prompt_tokens=8):
@@ -191,6 +216,7 @@ def main():
     total_steps = a.warmup + a.steps + table_steps
     max_len = max(len(p) for p in prompts) + total_steps * D + D
     n_pages = sum((len(p) + total_steps * D + D + 15) // 16 + 1 for p in prompts) if r.paged else 0
+    ceiling = copy_ceiling()
     side = torch.cuda.Stream() if a.graph else None
     with torch.cuda.stream(side):
         ctx = sdlm.Context(sdlm.model_cfg(m), max_batch=B, max_seq_len=max_len, block_D=D, tau=tau, paged=r.paged,
@@ -232,7 +258,8 @@ def main():
         pend = np.concatenate([np.zeros((1, B), np.int64), cnt.numpy().astype(np.int64)[:-1]], 0)[a.warmup:a.warmup + a.steps]
         R_mean = float((pend + D).sum(1).mean())
         w_bytes, kv_bytes = algorithmic_bytes(m, esz, float(ctx_timed.sum(1).mean()), R_mean)
-        results.append(dict(tau=tv, dt=dt, accepted=accepted, hist=hist, phases=phases, tphases=tphases, R_mean=R_mean,
+        lat = np.sort(np.array(run_tau.step_ms))
+        results.append(dict(tau=tv, dt=dt, lat=lat, accepted=accepted, hist=hist, phases=phases, tphases=tphases, R_mean=R_mean,
                             w_bytes=w_bytes, kv_bytes=kv_bytes, ctx_mean=float(ctx_timed.mean()), t_total=t_total))
     main_r = results[0]
     ms_per_step = 1e3 * main_r["dt"] / a.steps
@@ -281,6 +308,8 @@ def main():
             roof = dict(kernel=dom, bound="mfma", achieved=t["tflops"], peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
                         frac=t["tflops"] / PEAK_BF16_TFLOPS, traffic=None)
         roof["traffic"] = measured_traffic(a.config, dom)
+        if roof["bound"] == "hbm":
+            roof["frac_of_copy_ceiling"] = t["gbs"] / ceiling["GBs"]
         roof["avg_launch_us"] = t["avg_us"]
         roof["launches"] = t["launches"]
         roof["events"] = t["events"]
@@ -291,6 +320,11 @@ def main():
         "unit": "accepted tokens/s",
         "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": ms_per_step,
+        "step_latency_ms": {"median": float(np.median(main_r["lat"])), "p10": float(np.percentile(main_r["lat"], 10)),
+                            "p90": float(np.percentile(main_r["lat"], 90)), "min": float(main_r["lat"][0]),
+                            "max": float(main_r["lat"][-1]),
+                            "note": "device time between per-step events on the library's stream, timed steps only; the "
+                                    "context grows by the accepted tokens each step"},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if m.dtype == "fp32" else "bf16",
         "data": "synthetic",
@@ -307,6 +341,8 @@ def main():
         "step_algorithmic_GB": step_bytes / 1e9,
         "step_hbm_GBs": step_bytes / (ms_per_step * 1e-3) / 1e9,
         "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "hbm_copy_ceiling": ceiling,
+        "step_hbm_frac_of_copy_ceiling": step_bytes / (ms_per_step * 1e-3) / 1e9 / ceiling["GBs"],
         "roofline": roof,
         "kernels": {k: {kk: (round(vv, 3) if isinstance(vv, float) else vv) for kk, vv in v.items()} for k, v in table.items()},
         "prefill": {"prompt_tokens": int(sum(len(p) for p in prompts)), "seconds": round(run_tau.prefill_s, 3),
@@ -316,7 +352,7 @@ def main():
         "setup_s": {"weights": round(t_build, 1), "prefill_and_run": round(main_r["t_total"], 1)},
     }
     if a.verify is not None:    # the byte accounting above describes the block step alone
-        for k in ("step_algorithmic_GB", "step_hbm_GBs", "step_hbm_frac", "roofline"):
+        for k in ("step_algorithmic_GB", "step_hbm_GBs", "step_hbm_frac", "step_hbm_frac_of_copy_ceiling", "roofline"):
             out[k] = None
         out["verify_rows_per_step"] = B * ((D - 1) * D + (D - 2) * (D - 1) // 2)
     if len(results) > 1:
