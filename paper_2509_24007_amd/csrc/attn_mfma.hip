@@ -215,41 +215,70 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
 // launch rather than "the last workgroup merges": the chunks run on different XCDs, whose L2s only agree at
 // kernel boundaries, and a device-scope fence in every workgroup costs more than this launch.
 // grid (group, kv head, 16-query tile); the tile's scale factors are computed once and shared through LDS.
+// The kernel is a chain of dependent memory round trips and little else, so everything whose address follows from the
+// block index alone (the first chunks' partial results and running maxima) is requested before the group is looked
+// up: the partial-result area covers max_chunks chunks for every (group, head) of the grid, and what is fetched for
+// chunks or queries that do not exist is never used.
 __global__ __launch_bounds__(256) void attn_combine_k(AttnArgs a)
 {
-    const int g = blockIdx.x, hk = blockIdx.y, nq = blockIdx.z;
-    if (g >= a.rm.counts[1]) return;
-    const int row0 = a.rm.grp_row0[g], nrows = a.rm.grp_n[g];
+    constexpr int CU = 4, V4 = HD / 4, EPT = 16 * V4 / 256;   // chunks requested together; float4 per query; elements per thread
+    const int g = blockIdx.x, hk = blockIdx.y, nq = blockIdx.z, tid = threadIdx.x, lane = tid & 63;
+    const size_t item0 = ((size_t)g * a.kg.n_kv_heads + hk) * a.max_chunks;
+    const int n_groups = a.rm.counts[1];
+    const int row0 = a.rm.grp_row0[g], nrows = a.rm.grp_n[g];   // in bounds for every group of the grid
+    const int mq = tid & 15, mc = tid >> 4;
+    const float2 ml0 = a.part_ml[(item0 + min(mc, a.max_chunks - 1)) * QMAX + nq * 16 + mq];
+    f32x4 po[EPT][CU];
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int e = tid + j * 256, qi = nq * 16 + e / V4, d4 = (e % V4) * 4;
+#pragma unroll
+        for (int u = 0; u < CU; ++u) po[j][u] = *(const f32x4 *)(a.part_o + ((item0 + min(u, a.max_chunks - 1)) * QMAX + qi) * HD + d4);
+    }
+    if (g >= n_groups) return;
     const int QR = nrows * a.G;
     if (nq * 16 >= QR) return;
-    int lim = 0;
-    for (int i = 0; i < nrows; ++i) lim = max(lim, a.rm.lim[row0 + i]);
+    int lim = lane < nrows ? a.rm.lim[row0 + lane] : 0;   // a group has at most QMAX rows: every wavefront finds the maximum itself
+    for (int o = 32; o > 0; o >>= 1) lim = max(lim, __shfl_xor(lim, o));
     const int n_pages = (lim + PAGE - 1) / PAGE;
     const int n_chunks = max(1, (n_pages + a.chunk_pages - 1) / a.chunk_pages);
     if (n_chunks == 1) return;   // the attention kernel wrote the final result itself
-    const size_t item0 = ((size_t)g * a.kg.n_kv_heads + hk) * a.max_chunks;
-    __shared__ float sf[16][65];   // [query][chunk]: 2^{c(m_c - M)} / L
-    const int tid = threadIdx.x;
+    __shared__ float sf[16][65], sl[16][65];   // [query][chunk]: running maximum, then 2^{c(m_c - M)} / L; row sum
+    for (int c = mc; c < n_chunks; c += 16) {
+        const float2 ml = c < 16 ? ml0 : a.part_ml[(item0 + c) * QMAX + nq * 16 + mq];
+        sf[mq][c] = ml.x;
+        sl[mq][c] = ml.y;
+    }
+    __syncthreads();
     if (tid < 16 && nq * 16 + tid < QR) {
-        const int qi = nq * 16 + tid;
         float M = -INFINITY;
-        for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, a.part_ml[(item0 + c) * QMAX + qi].x);
+        for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, sf[tid][c]);
         float L = 0.f;
         for (int c = 0; c < n_chunks; ++c) {
-            float2 ml = a.part_ml[(item0 + c) * QMAX + qi];
-            float f = ml.x == -INFINITY ? 0.f : exp2f((ml.x - M) * a.c);
+            const float m = sf[tid][c];
+            const float f = m == -INFINITY ? 0.f : exp2f((m - M) * a.c);
             sf[tid][c] = f;
-            L += ml.y * f;
+            L += sl[tid][c] * f;
         }
         const float inv = 1.0f / L;
         for (int c = 0; c < n_chunks; ++c) sf[tid][c] *= inv;
     }
     __syncthreads();
-    for (int e = tid; e < 16 * (HD / 4); e += 256) {
-        const int ql = e / (HD / 4), d4 = (e % (HD / 4)) * 4, qi = nq * 16 + ql;
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const int e = tid + j * 256, ql = e / V4, d4 = (e % V4) * 4, qi = nq * 16 + ql;
         if (qi >= QR) continue;
         f32x4 o = {0.f, 0.f, 0.f, 0.f};
-        for (int c = 0; c < n_chunks; ++c) o += *(const f32x4 *)(a.part_o + ((item0 + c) * QMAX + qi) * HD + d4) * sf[ql][c];
+        for (int c0 = 0; c0 < n_chunks; c0 += CU) {
+            if (c0 > 0) {
+#pragma unroll
+                for (int u = 0; u < CU; ++u)
+                    po[j][u] = *(const f32x4 *)(a.part_o + ((item0 + min(c0 + u, n_chunks - 1)) * QMAX + qi) * HD + d4);
+            }
+#pragma unroll
+            for (int u = 0; u < CU; ++u)
+                if (c0 + u < n_chunks) o += po[j][u] * sf[ql][c0 + u];
+        }
         const int rl = qi / a.G, hg = qi % a.G;
         bf16_t *op = a.out + ((size_t)(row0 + rl) * a.Hq + hk * a.G + hg) * HD + d4;
         *(uint2 *)op = make_uint2(pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3]));

@@ -192,9 +192,27 @@ __global__ __launch_bounds__(256) void rmsnorm_k(T *out, float *x, const T *g, i
             } else {
                 gv[i] = *(const float4 *)(g + k);
             }
-            for (int sl = 0; sl < n_slabs; ++sl) {
-                float4 p = *(const float4 *)(slabs + sl * slab_stride + (size_t)row * h + k);
-                v[i].x += p.x; v[i].y += p.y; v[i].z += p.z; v[i].w += p.w;
+        }
+    }
+    // The slabs are added in slab order, but requested SU at a time: one memory round trip per SU slabs instead of one
+    // per slab.  A slab index past the end is clamped for the load (a valid address, a cache hit) and its add skipped.
+    constexpr int SU = NV <= 4 ? 4 : (NV == 8 ? 2 : 1);
+    for (int s0 = 0; s0 < n_slabs; s0 += SU) {
+        float4 p[SU][NV];
+#pragma unroll
+        for (int u = 0; u < SU; ++u) {
+            const int sl = min(s0 + u, n_slabs - 1);
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                const int k = (i * 256 + threadIdx.x) * 4;
+                p[u][i] = k < h ? *(const float4 *)(slabs + sl * slab_stride + (size_t)row * h + k) : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < SU; ++u) {
+            if (s0 + u < n_slabs) {
+#pragma unroll
+                for (int i = 0; i < NV; ++i) { v[i].x += p[u][i].x; v[i].y += p[u][i].y; v[i].z += p[u][i].z; v[i].w += p[u][i].w; }
             }
         }
     }
@@ -326,9 +344,20 @@ __global__ __launch_bounds__(256) void rope_scatter_k(const float *qkv, int n_sl
     const int head = blockIdx.y * 4 + (threadIdx.x >> 6), i = threadIdx.x & 63;   // heads: Hq of q, then Hkv of k, then Hkv of v
     if (head >= Hq + 2 * Hk || i >= half || (r >= sure && r >= rm.counts[0])) return;   // certain rows: no wait for the count
     const float *src = qkv + (size_t)r * (nq + 2 * nk) + head * d + i;
+    const int pos = rm.pos[r], kind = rm.kind[r], b = rm.seq[r], stg = rm.stg[r];   // requested together with the projections
     float x0 = src[0], x1 = src[half];
-    for (int sl = 1; sl < n_slabs; ++sl) { x0 += src[sl * slab_stride]; x1 += src[sl * slab_stride + half]; }
-    const int pos = rm.pos[r], kind = rm.kind[r], b = rm.seq[r], stg = rm.stg[r];
+    for (int s0 = 1; s0 < n_slabs; s0 += 4) {   // four slabs per memory round trip, added in slab order
+        float p0[4], p1[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const size_t o = (size_t)min(s0 + u, n_slabs - 1) * slab_stride;
+            p0[u] = src[o];
+            p1[u] = src[o + half];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (s0 + u < n_slabs) { x0 += p0[u]; x1 += p1[u]; }
+    }
     if (head < Hq) {
         const float2 t = rope[(size_t)pos * half + i];
         T *q = q_out + (size_t)r * nq + head * d + i;
