@@ -37,6 +37,7 @@ struct AttnArgs {
     float *part_o;      // [item][QMAX][HD]
     float2 *part_ml;    // [item][QMAX]
     float c;            // log2(e) / sqrt(d)
+    bool early;         // merge kernel: request the first chunks' partials before the group is looked up
 };
 
 union Op8 { bf16x8 v; uint4 u; uint2 h[2]; uint32_t w[4]; };
@@ -218,7 +219,8 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
 // The kernel is a chain of dependent memory round trips and little else, so everything whose address follows from the
 // block index alone (the first chunks' partial results and running maxima) is requested before the group is looked
 // up: the partial-result area covers max_chunks chunks for every (group, head) of the grid, and what is fetched for
-// chunks or queries that do not exist is never used.
+// chunks or queries that do not exist is never used.  Only worth it for the small grids of a decode step (a.early):
+// in a prefill pass most (group, head) items have a single chunk and the early requests would be wasted traffic.
 __global__ __launch_bounds__(256) void attn_combine_k(AttnArgs a)
 {
     constexpr int CU = 4, V4 = HD / 4, EPT = 16 * V4 / 256;   // chunks requested together; float4 per query; elements per thread
@@ -227,10 +229,12 @@ __global__ __launch_bounds__(256) void attn_combine_k(AttnArgs a)
     const int n_groups = a.rm.counts[1];
     const int row0 = a.rm.grp_row0[g], nrows = a.rm.grp_n[g];   // in bounds for every group of the grid
     const int mq = tid & 15, mc = tid >> 4;
-    const float2 ml0 = a.part_ml[(item0 + min(mc, a.max_chunks - 1)) * QMAX + nq * 16 + mq];
+    float2 ml0 = make_float2(0.f, 0.f);
     f32x4 po[EPT][CU];
+    if (a.early) ml0 = a.part_ml[(item0 + min(mc, a.max_chunks - 1)) * QMAX + nq * 16 + mq];
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
+        if (!a.early) break;
         const int e = tid + j * 256, qi = nq * 16 + e / V4, d4 = (e % V4) * 4;
 #pragma unroll
         for (int u = 0; u < CU; ++u) po[j][u] = *(const f32x4 *)(a.part_o + ((item0 + min(u, a.max_chunks - 1)) * QMAX + qi) * HD + d4);
@@ -245,7 +249,7 @@ __global__ __launch_bounds__(256) void attn_combine_k(AttnArgs a)
     if (n_chunks == 1) return;   // the attention kernel wrote the final result itself
     __shared__ float sf[16][65], sl[16][65];   // [query][chunk]: running maximum, then 2^{c(m_c - M)} / L; row sum
     for (int c = mc; c < n_chunks; c += 16) {
-        const float2 ml = c < 16 ? ml0 : a.part_ml[(item0 + c) * QMAX + nq * 16 + mq];
+        const float2 ml = (c < 16 && a.early) ? ml0 : a.part_ml[(item0 + c) * QMAX + nq * 16 + mq];
         sf[mq][c] = ml.x;
         sl[mq][c] = ml.y;
     }
@@ -270,7 +274,7 @@ __global__ __launch_bounds__(256) void attn_combine_k(AttnArgs a)
         if (qi >= QR) continue;
         f32x4 o = {0.f, 0.f, 0.f, 0.f};
         for (int c0 = 0; c0 < n_chunks; c0 += CU) {
-            if (c0 > 0) {
+            if (c0 > 0 || !a.early) {
 #pragma unroll
                 for (int u = 0; u < CU; ++u)
                     po[j][u] = *(const f32x4 *)(a.part_o + ((item0 + min(c0 + u, n_chunks - 1)) * QMAX + qi) * HD + d4);
@@ -342,6 +346,7 @@ bool launch_attn_mfma(hipStream_t s, const sdlm_model_cfg *m, int max_seq_len, c
     a.part_o = (float *)scratch;
     a.part_ml = (float2 *)((char *)scratch + items * QMAX * HD * 4);
     a.c = 1.4426950408889634f / sqrtf((float)HD);
+    a.early = (long)max_groups * kg.n_kv_heads * NQ <= 4096;
     if (part == 0) hipLaunchKernelGGL(attn_mfma_k, dim3(max_groups, kg.n_kv_heads, a.max_chunks), dim3(256), 0, s, a);
     else if (a.max_chunks > 1) hipLaunchKernelGGL(attn_combine_k, dim3(max_groups, kg.n_kv_heads, NQ), dim3(256), 0, s, a);
     return a.max_chunks > 1;

@@ -450,6 +450,78 @@ __global__ __launch_bounds__(256) void lm_combine_k(const float4 *part, int n_bl
     }
 }
 
+// ------------------------------------------------------------------------------------------------ gate/up for <= 32 rows
+// The step of a single sequence has at most 2D <= 32 rows, and the gate/up projection cannot be split along k between
+// workgroups (SiLU(gate) * up needs complete sums): the tiled kernel above would run it as N/128 workgroups, far too
+// few to keep the weight stream busy.  Here a workgroup owns one 32-feature block (its gate tile and its up tile),
+// its four wavefronts each take a quarter of k, and the quarters are added in wavefront order through LDS.  Both
+// operands come straight from global memory in the MFMA operand order: the weights as a contiguous run, the rows
+// (at most 32 x K, shared by every workgroup, so served by L2) 16 bytes per lane and k step; rows beyond the live
+// ones repeat the last row and their results are dropped.  Loads are issued eight k steps at a time into two register
+// sets: sixteen k steps (48 KB per wavefront) are in flight before the first MFMA.
+constexpr int SK_U = 8, SK_W = 4;   // k steps per register set; wavefronts (measured: eight wavefronts are slower)
+
+__global__ __launch_bounds__(SK_W * 64) void swiglu_skinny_k(MfmaArgs a)
+{
+    __shared__ float part[SK_W][2][16][64];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int j = blockIdx.x;   // features 32j .. 32j+31: tiles 2j (gate) and 2j+1 (up) of the fused matrix
+    const int KS = a.K >> 4, per = (KS + SK_W - 1) / SK_W;
+    const int k_begin = wave * per, k_end = min(KS, k_begin + per);
+    const bf16_t *wg = a.Wp + ((size_t)(2 * j) * KS) * 512 + lane * 8, *wu = wg + (size_t)KS * 512;
+    bf16x8 g0[SK_U], u0[SK_U], x0[SK_U], g1[SK_U], u1[SK_U], x1[SK_U];
+#define SDLM_SK_LOAD_W(G, U, kb) \
+    _Pragma("unroll") for (int u = 0; u < SK_U; ++u) { \
+        const size_t o = (size_t)min((kb) + u, KS - 1) * 512; \
+        G[u] = *(const bf16x8 *)(wg + o); U[u] = *(const bf16x8 *)(wu + o); }
+#define SDLM_SK_LOAD_X(X, kb) \
+    _Pragma("unroll") for (int u = 0; u < SK_U; ++u) X[u] = *(const bf16x8 *)(xp + min((kb) + u, KS - 1) * 16);
+#define SDLM_SK_MMA(G, U, X, kb) \
+    _Pragma("unroll") for (int u = 0; u < SK_U; ++u) if ((kb) + u < k_end) { \
+        ag = __builtin_amdgcn_mfma_f32_32x32x16_bf16(G[u], X[u], ag, 0, 0, 0); \
+        au = __builtin_amdgcn_mfma_f32_32x32x16_bf16(U[u], X[u], au, 0, 0, 0); }
+    SDLM_SK_LOAD_W(g0, u0, k_begin)   // the weights do not wait for the row count
+    if (k_begin + SK_U < k_end) { SDLM_SK_LOAD_W(g1, u1, k_begin + SK_U) }
+    const int R = min(*a.pR, a.max_rows);
+    if (R <= 0) return;
+    const bf16_t *xp = a.X + (size_t)min(lane & 31, R - 1) * a.K + (lane >> 5) * 8;
+    SDLM_SK_LOAD_X(x0, k_begin)
+    if (k_begin + SK_U < k_end) { SDLM_SK_LOAD_X(x1, k_begin + SK_U) }
+    f32x16 ag, au;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { ag[v] = 0.f; au[v] = 0.f; }
+    for (int k0 = k_begin; k0 < k_end; k0 += 2 * SK_U) {
+        SDLM_SK_MMA(g0, u0, x0, k0)
+        if (k0 + 2 * SK_U < k_end) { SDLM_SK_LOAD_W(g0, u0, k0 + 2 * SK_U) SDLM_SK_LOAD_X(x0, k0 + 2 * SK_U) }
+        SDLM_SK_MMA(g1, u1, x1, k0 + SK_U)
+        if (k0 + 3 * SK_U < k_end) { SDLM_SK_LOAD_W(g1, u1, k0 + 3 * SK_U) SDLM_SK_LOAD_X(x1, k0 + 3 * SK_U) }
+    }
+#undef SDLM_SK_LOAD_W
+#undef SDLM_SK_LOAD_X
+#undef SDLM_SK_MMA
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { part[wave][0][v][lane] = ag[v]; part[wave][1][v][lane] = au[v]; }
+    __syncthreads();
+    // accumulator element v of lane l: feature 8*(v/4) + 4*(l/32) + v%4 of the block, activation row l%32;
+    // wavefront w finishes the elements EL*w .. EL*w + EL-1 of every lane: EL consecutive features of one row
+    constexpr int EL = 16 / SK_W;
+    static_assert(EL == 2 || EL == 4, "an output store is one or two bf16 pairs");
+    const int row = lane & 31, v0 = wave * EL, n = j * 32 + (v0 >> 2) * 8 + (lane >> 5) * 4 + (v0 & 3);
+    if (row >= R || n >= a.N) return;
+    float o[EL];
+#pragma unroll
+    for (int e = 0; e < EL; ++e) {
+        float gs = part[0][0][v0 + e][lane], us = part[0][1][v0 + e][lane];
+#pragma unroll
+        for (int w = 1; w < SK_W; ++w) { gs += part[w][0][v0 + e][lane]; us += part[w][1][v0 + e][lane]; }
+        o[e] = silu_f(gs) * us;
+    }
+    bf16_t *dst = a.Yt + (size_t)row * a.n_out + n;
+    if constexpr (EL == 4) *(uint2 *)dst = make_uint2(pack_bf16(o[0], o[1]), pack_bf16(o[2], o[3]));
+    else *(uint32_t *)dst = pack_bf16(o[0], o[EL - 1]);
+}
+
 // ------------------------------------------------------------------------------------------------ launch policy
 struct TileChoice { int MT, NT, splits; };
 
@@ -543,6 +615,10 @@ int launch_gemm_mfma(hipStream_t s, int epi, const GemmArgs &g, float *slabs, si
     a.Yf = g.Yf; a.Yt = (bf16_t *)g.Yt; a.pR = g.pR; a.max_rows = g.max_rows; a.N = g.N; a.K = g.K; a.scale = g.scale;
     a.n_out = g.N;
     a.n_tiles = epi == EPI_SWIGLU ? 2 * (int)(mfma_pad_n(g.N) / 32) : (int)(mfma_pad_n(g.N) / 32);
+    if (epi == EPI_SWIGLU && g.max_rows <= 32) {
+        hipLaunchKernelGGL(swiglu_skinny_k, dim3(a.n_tiles / 2), dim3(SK_W * 64), 0, s, a);
+        return 1;
+    }
     TileChoice c = choose(epi, g.max_rows, g.min_rows, g.N, g.K, slab_room_floats);
     a.slab = (size_t)g.max_rows * g.N;
     if (c.splits > 1) a.Yf = slabs;

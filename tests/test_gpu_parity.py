@@ -482,6 +482,29 @@ def test_mfma_row_blocks_beyond_the_sure_ones():
     ctx.close()
 
 
+@pytest.mark.parametrize("B,D,hidden,ffn", [(1, 1, 128, 192), (1, 4, 320, 576), (3, 4, 448, 1088), (4, 4, 1088, 320), (2, 8, 192, 2112)])
+def test_bf16_gate_up_of_at_most_32_rows(B, D, hidden, ffn):
+    """Steps of at most 32 rows (B * 2D <= 32) take the gate/up kernel that splits k over the wavefronts of a workgroup:
+    k extents whose per-wavefront share is shorter than, equal to and longer than the two register sets, not a multiple
+    of a set, and row counts from 1 to the full 32."""
+    m = mfma_cfg(n_q_heads=4, n_kv_heads=2, hidden=hidden, ffn=ffn, vocab=1000, has_qkv_bias=True)
+    # (wide layers with weights of std 0.05 saturate the activations: bf16 noise alone then passes the logit bound, in
+    # either gate/up kernel)
+    om, g_dev, layers_dev = both_models(m, seed=70 + B + D, std=0.05 if hidden < 1000 else 0.03)
+    lens = [5 + 7 * i for i in range(B)]
+    prompts = [syn.uniform_int(5, f"sk{i}", n, 0, m.vocab - 1).numpy() for i, n in enumerate(lens)]
+    steps = 4
+    ids, cnt = syn.make_overrides(21, steps, B, D, m.vocab)
+    cnt = cnt.clone()
+    cnt[1] = D                                       # the step after a full commit has B * 2D rows
+    max_len = max(lens) + steps * D + D
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=B, max_seq_len=max_len, D=D, tau=0.5)
+    assert ctx.kernel_info == "mfma-bf16"
+    st, _ = lockstep(ctx, om, prompts, D, 0.5, steps, logit_tol=2e-2, conf_tol=1e-3, overrides=(ids, cnt), bf16=True, max_len=max_len)
+    print("gate/up <= 32 rows", (B, D, hidden, ffn), st)
+    ctx.close()
+
+
 # ------------------------------------------------------------------ seeded random shapes
 def _random_case(seed):
     rng = np.random.RandomState(seed)
