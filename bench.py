@@ -51,6 +51,10 @@ def parse():
                     help="phases bracketed by HIP events inside the timed region: one phase name (default: the dominant kernel), "
                          "main (all six big kernels, ~6%% slower steps) or none; the per-kernel table of the other phases comes "
                          "from up to 32 extra untimed steps")
+    ap.add_argument("--profile-every", type=int, default=9,
+                    help="inside the timed region only every n-th launch of a bracketed phase carries its two event records "
+                         "(an event record between two kernels keeps them from running back to back); 9 is coprime to the "
+                         "layer counts, so the samples rotate through the layers")
     ap.add_argument("--conf-fn", type=int, default=0, choices=(0, 1), help="0: softmax probability of the arg-max token; 1: entropy-normalised confidence")
     ap.add_argument("--accept-rule", type=int, default=0, choices=(0, 1), help="0: cumulative product >= tau (the paper's rule); 1: every leading confidence >= tau")
     ap.add_argument("--block-causal", action="store_true", help="the causal-in-block ablation instead of mutual attention inside the block")
@@ -100,7 +104,7 @@ def algorithmic_bytes(m, esz, lens_sum, R):
     return weights, kv
 
 
-def run_tau(ctx, m, r, prompts, tau_idx, steps, warmup, prof_phases, table_steps=0, verify=None, force=0):
+def run_tau(ctx, m, r, prompts, tau_idx, steps, warmup, prof_phases, table_steps=0, verify=None, force=0, every=1):
     """Warm-up, then the timed region (only `prof_phases` carry events: every bracketed phase costs two event records
     per launch), then `table_steps` untimed extra steps with every main phase bracketed for the per-kernel table."""
     import torch
@@ -126,7 +130,7 @@ def run_tau(ctx, m, r, prompts, tau_idx, steps, warmup, prof_phases, table_steps
     for t in range(warmup):
         one(t)
     torch.cuda.synchronize()
-    ctx.profile(prof_phases)
+    ctx.profile(prof_phases, every)
     # one event per step on the library's stream: the spread of the step's device time (median, p10, p90)
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t0 = time.perf_counter()
@@ -244,7 +248,7 @@ def main():
                 ctx.graph(True)
             build_model(ctx, m, wl.seed)
         t0 = time.perf_counter()
-        dt, cnt, phases, n_end, tphases = run_tau(ctx, m, r, prompts, ti, a.steps, a.warmup, prof, table_steps if ti == 0 else 0, a.verify, a.force_accept)
+        dt, cnt, phases, n_end, tphases = run_tau(ctx, m, r, prompts, ti, a.steps, a.warmup, prof, table_steps if ti == 0 else 0, a.verify, a.force_accept, a.profile_every)
         t_total = time.perf_counter() - t0
         if a.force_accept:
             cnt = torch.full_like(cnt, a.force_accept)
@@ -312,6 +316,7 @@ def main():
             roof["frac_of_copy_ceiling"] = t["gbs"] / ceiling["GBs"]
         roof["avg_launch_us"] = t["avg_us"]
         roof["launches"] = t["launches"]
+        roof["sampled_every"] = a.profile_every if t["events"] == "timed region" else 1
         roof["events"] = t["events"]
     step_bytes = main_r["w_bytes"] + main_r["kv_bytes"]
     out = {

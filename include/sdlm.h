@@ -233,6 +233,13 @@ int32_t sdlm_max_rows(const sdlm_ctx *ctx);
 enum { SDLM_PH_ROWS = 0, SDLM_PH_NORM, SDLM_PH_QKV, SDLM_PH_ROPE, SDLM_PH_ATTN, SDLM_PH_OPROJ, SDLM_PH_GATEUP,
        SDLM_PH_DOWN, SDLM_PH_LMHEAD, SDLM_PH_ACCEPT, SDLM_PH_ATTN_MERGE /* merge of the split-KV partials */, SDLM_N_PHASES };
 int sdlm_profile(sdlm_ctx *ctx, int32_t mask);
+/*
+ * Sampling: bracket only every n-th launch of a selected phase (n >= 1, default 1), counted per phase from this call
+ * on.  An event record between two kernels keeps them from running back to back, so timing every launch of a phase
+ * that runs once per layer slows the step it measures; with n coprime to the layer count the samples rotate through
+ * the layers.  sdlm_profile_read then reports the sampled launches only.  Errors: SDLM_EINVAL.
+ */
+int sdlm_profile_every(sdlm_ctx *ctx, int32_t n);
 int sdlm_profile_read(sdlm_ctx *ctx, float *ms, int32_t *launches);
 
 /* Which kernel family serves the GEMMs and the attention: "generic-fp32", "mfma-bf16", ... ([host] string). */

@@ -164,6 +164,8 @@ struct sdlm_ctx {
     void *graph_key[4] = {nullptr, nullptr, nullptr, nullptr};   // the output pointers baked into the captured launches
     // profiling
     uint32_t prof = 0;                   // bit p: phase p is bracketed by events
+    uint32_t prof_every = 1;             // ... on every prof_every-th launch of the phase
+    uint32_t prof_seen[SDLM_N_PHASES] = {};
     std::vector<hipEvent_t> ev;          // pairs
     std::vector<int> ev_phase;
     size_t ev_used = 0;
@@ -195,6 +197,7 @@ struct Phase {
     Phase(sdlm_ctx *c_, int ph) : c(c_)
     {
         if (!((c->prof >> ph) & 1u)) return;
+        if (c->prof_seen[ph]++ % c->prof_every != 0) return;
         if (c->ev_used + 2 > c->ev.size()) {
             hipEvent_t a, b;
             if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
@@ -737,6 +740,15 @@ int sdlm_profile(sdlm_ctx *c, int32_t enable)
 {
     if (!c) return SDLM_EINVAL;
     c->prof = (uint32_t)enable;
+    return SDLM_OK;
+}
+
+int sdlm_profile_every(sdlm_ctx *c, int32_t n)
+{
+    if (!c) return SDLM_EINVAL;
+    if (n < 1) return fail(c, SDLM_EINVAL, "sdlm_profile_every: n must be at least 1 (got %d)", n);
+    c->prof_every = (uint32_t)n;
+    for (int p = 0; p < SDLM_N_PHASES; ++p) c->prof_seen[p] = 0;
     return SDLM_OK;
 }
 

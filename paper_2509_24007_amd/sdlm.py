@@ -20,7 +20,7 @@ OK, EINVAL, ECAPACITY, ESTATE, EHIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("sdlm_workspace_bytes", "sdlm_create", "sdlm_init_weights", "sdlm_prefill", "sdlm_decode_step",
            "sdlm_graph", "sdlm_verify_step", "sdlm_kv_commit", "sdlm_get_lengths", "sdlm_debug_tap", "sdlm_debug_rows", "sdlm_debug_read_kv",
-           "sdlm_debug_gemm_plan", "sdlm_max_rows", "sdlm_profile", "sdlm_profile_read", "sdlm_kernel_info", "sdlm_last_error",
+           "sdlm_debug_gemm_plan", "sdlm_max_rows", "sdlm_profile", "sdlm_profile_every", "sdlm_profile_read", "sdlm_kernel_info", "sdlm_last_error",
            "sdlm_destroy")
 
 
@@ -90,6 +90,8 @@ def load():
     L.sdlm_max_rows.argtypes = [vp]
     L.sdlm_profile.restype = C.c_int
     L.sdlm_profile.argtypes = [vp, i32]
+    L.sdlm_profile_every.restype = C.c_int
+    L.sdlm_profile_every.argtypes = [vp, i32]
     L.sdlm_profile_read.restype = C.c_int
     L.sdlm_profile_read.argtypes = [vp, vp, vp]
     L.sdlm_kernel_info.restype = C.c_char_p
@@ -302,8 +304,10 @@ class Context:
         torch.cuda.synchronize(self.device)
         return k.cpu(), v.cpu()
 
-    def profile(self, phases=None) -> None:
-        """phases: None/False -> off, True -> all, or an iterable of phase names to bracket with events."""
+    def profile(self, phases=None, every: int = 1) -> None:
+        """phases: None/False -> off, True -> all, or an iterable of phase names to bracket with events; every: only
+        every n-th launch of a phase is bracketed."""
+        self._check(self.L.sdlm_profile_every(self.h, int(every)))
         if phases is None or phases is False:
             mask = 0
         elif phases is True:

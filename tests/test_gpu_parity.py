@@ -311,6 +311,32 @@ def test_verify_position_independent_model_accepts_whole_block():
     ctx.close()
 
 
+def test_phase_timers_count_launches_and_sample():
+    """The per-phase event timers report one launch per layer and step for a per-layer phase, every n-th of them when
+    sampling, and the sampled steps produce the same tokens as the untimed ones."""
+    m = mfma_cfg(n_layers=3)
+    om, g_dev, layers_dev = both_models(m, seed=8, std=0.05)
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=2, max_seq_len=64, D=4, tau=0.5)
+    prompts = [np.array([1, 2, 3], dtype=np.int32), np.array([4, 5], dtype=np.int32)]
+    ids = torch.empty(3, 2, 4, dtype=torch.int32, device="cuda")
+    cnt = torch.empty(3, 2, dtype=torch.int32, device="cuda")
+    from paper_2509_24007_amd.sdlm import SdlmError
+    for mode, (every, steps) in enumerate([(1, 2), (2, 3), (7, 2)]):
+        ctx.prefill(prompts)
+        ctx.profile(["gateup", "lmhead"], every=every)
+        for _ in range(steps):
+            ctx.decode_step(ids[mode], cnt[mode])
+        got = ctx.profile_read()
+        ctx.profile(None)
+        assert got["gateup"][1] == -(-3 * steps // every) and got["lmhead"][1] == -(-steps // every)
+        assert got["gateup"][0] > 0.0 and got["qkv"] == (0.0, 0)
+    torch.cuda.synchronize()
+    assert ids[0].eq(ids[1]).all() and ids[0].eq(ids[2]).all() and cnt[0].eq(cnt[1]).all() and cnt[0].eq(cnt[2]).all()
+    with pytest.raises(SdlmError):
+        ctx.profile(["gateup"], every=0)
+    ctx.close()
+
+
 def test_verify_error_paths():
     m = gpu_cfg()
     om, g_dev, layers_dev = both_models(m, seed=6, std=0.3)
