@@ -531,6 +531,19 @@ def test_bf16_gate_up_of_at_most_32_rows(B, D, hidden, ffn):
     ctx.close()
 
 
+@pytest.mark.parametrize("hidden", [4100, 8200, 16384])
+def test_fp32_wide_hidden_rows(hidden):
+    """Rows wider than 4096 elements: the RMSNorm variants that hold 8 and 16 vectors of a row per thread (and the
+    widest row the library accepts)."""
+    m = gpu_cfg(hidden=hidden, n_layers=1, ffn=48, vocab=97)
+    om, g_dev, layers_dev = both_models(m, seed=33, std=0.02)
+    prompts = [np.array([3, 1, 4, 1, 5], dtype=np.int32), np.array([9, 2], dtype=np.int32)]
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=2, max_seq_len=32, D=3, tau=0.5)
+    st, _ = lockstep(ctx, om, prompts, 3, 0.5, 3, logit_tol=1e-4, conf_tol=1e-5)
+    print("wide rows", hidden, st)
+    ctx.close()
+
+
 # ------------------------------------------------------------------ seeded random shapes
 def _random_case(seed):
     rng = np.random.RandomState(seed)
