@@ -194,9 +194,9 @@ __global__ __launch_bounds__(256) void rmsnorm_k(T *out, float *x, const T *g, i
             }
         }
     }
-    // The slabs are added in slab order, but requested SU at a time: one memory round trip per SU slabs instead of one
-    // per slab.  A slab index past the end is clamped for the load (a valid address, a cache hit) and its add skipped.
-    constexpr int SU = NV <= 4 ? 4 : (NV == 8 ? 2 : 1);
+    // The slabs are added in slab order, but requested SU at a time (as many as the registers of the row width allow): one
+    // memory round trip per SU slabs instead of one per slab.  A slab index past the end is clamped for the load (a valid address, a cache hit) and its add skipped.
+    constexpr int SU = NV <= 2 ? 8 : (NV <= 4 ? 4 : (NV == 8 ? 2 : 1));
     for (int s0 = 0; s0 < n_slabs; s0 += SU) {
         float4 p[SU][NV];
 #pragma unroll
