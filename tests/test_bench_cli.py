@@ -1,0 +1,13 @@
+"""Host-side behaviour of bench.py that needs no GPU."""
+import os
+import subprocess
+import sys
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    """This build measures one GPU: --gpus N with N > 1 exits before anything touches a device."""
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert p.returncode == 2
+    assert "ONE GPU" in p.stderr and p.stdout.strip() == ""
