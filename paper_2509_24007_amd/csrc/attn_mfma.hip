@@ -9,8 +9,8 @@
 // workgroup copies a tile pair (32 keys, 16 KB) global -> LDS as one contiguous run and every wavefront reads its
 // operands from LDS with conflict-free 16-byte / 8-byte reads.  Each of the four wavefronts owns 16 of the (at
 // most 64) query vectors, so its state is small (32 accumulator registers) and four workgroups fit on a CU.
-// The mask of the method lives in registers: every row sees cache keys [0, lim) and the first slim slots of the
-// group's staging tile.  A pending row at position p has lim = p + 1 and no staging slots; a block row has lim = s
+// The mask of the method lives in registers: every row sees cache keys [0, lim) and the slots of the group's
+// staging tile that its slot mask names.  A pending row at position p has lim = p + 1 and no staging slots; a block row has lim = s
 // and the D keys of its own block in the staging tile.
 // Chunks of one (group, head) are merged by a second small kernel when there is more than one.
 #include "mfma.hpp"
@@ -61,7 +61,7 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
     for (int u = 0; u < 4; ++u) pg_first[u] = ptab[min(chunk * a.chunk_pages + u, a.kg.pages_per_seq - 1)];
 
     int lim_l = lane < nrows ? a.rm.lim[row0 + lane] : 0;
-    int blk_l = lane < nrows ? (a.rm.slim[row0 + lane] > 0 ? 1 : 0) : 0;
+    int blk_l = lane < nrows ? (a.rm.smask[row0 + lane] != 0 ? 1 : 0) : 0;
     int min_l = lane < nrows ? lim_l : 0x7fffffff;
     for (int o = 32; o > 0; o >>= 1) {
         lim_l = max(lim_l, __shfl_xor(lim_l, o));
@@ -83,7 +83,7 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
     const bool wave_active = wave * 16 < QR;
     const int rl = qvalid ? qi / G : 0, hg = qvalid ? qi % G : 0, qrow = row0 + rl;
     const int lim_q = qvalid ? a.rm.lim[qrow] : 0;
-    const int slim_q = qvalid ? a.rm.slim[qrow] : 0;   // staging slots this query sees
+    const uint32_t smask_q = qvalid ? (uint32_t)a.rm.smask[qrow] : 0u;   // staging slots this query sees
     Op8 qop[4];
     {
         const bf16_t *qp = a.q + ((size_t)qrow * a.Hq + hk * G + hg) * HD + lg * 8;
@@ -152,8 +152,8 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
                 const int keyA = (c0 + uA) * PAGE + lg * 4, keyB = (c0 + uB) * PAGE + lg * 4;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    bool visA = stgA ? (lg * 4 + v < slim_q) : (keyA + v < lim_q);
-                    bool visB = hasB && (stgB ? (lg * 4 + v < slim_q) : (keyB + v < lim_q));
+                    bool visA = stgA ? ((smask_q >> (lg * 4 + v)) & 1u) != 0 : (keyA + v < lim_q);
+                    bool visB = hasB && (stgB ? ((smask_q >> (lg * 4 + v)) & 1u) != 0 : (keyB + v < lim_q));
                     sA[v] = visA ? sA[v] : -INFINITY;
                     sB[v] = visB ? sB[v] : -INFINITY;
                 }

@@ -61,7 +61,7 @@ __host__ __device__ inline int v_off(int slot, int i) { return (((i >> 4) << 2) 
 struct RowMeta {
     int32_t *tok, *pos, *seq, *kind, *lim;  // [max_rows]; kind: -1 = K/V go to the cache slot of pos, else the slot in the
                                             // row's staging tile; lim: visible cache keys [0, lim)
-    int32_t *stg, *slim;                    // [max_rows]; staging tile of the row (-1: none) and how many of its slots the row sees
+    int32_t *stg, *smask;                   // [max_rows]; staging tile of the row (-1: none) and which of its 16 slots the row sees (bit i: slot i)
     int32_t *grp_row0, *grp_n, *grp_seq;    // [max_groups]: runs of <= GROUP_ROWS rows of one sequence that share a staging tile
     int32_t *grp_stg;                       // [max_groups]: that staging tile (-1: none)
     int32_t *blk_row;                       // [max_batch*D]: packed row index of the rows that go through the LM head

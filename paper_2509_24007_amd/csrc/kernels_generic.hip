@@ -30,12 +30,12 @@ __global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mas
         for (int i = 0; i < p; ++i, ++r) {
             rm.tok[r] = st.pend_tok[b * D + i];
             rm.pos[r] = c + i; rm.seq[r] = b; rm.kind[r] = -1; rm.lim[r] = c + i + 1;
-            rm.stg[r] = -1; rm.slim[r] = 0;
+            rm.stg[r] = -1; rm.smask[r] = 0;
         }
         for (int j = 0; j < D; ++j, ++r) {
             rm.tok[r] = j == 0 ? st.last_tok[b] : mask_id;
             rm.pos[r] = n - 1 + j; rm.seq[r] = b; rm.kind[r] = j; rm.lim[r] = n - 1;
-            rm.stg[r] = stg0 + b; rm.slim[r] = causal ? j + 1 : D;   // block keys: all D, or (causal variant) up to the row itself
+            rm.stg[r] = stg0 + b; rm.smask[r] = (1 << (causal ? j + 1 : D)) - 1;   // block keys: all D, or (causal variant) up to the row itself
             rm.blk_row[b * D + j] = r;
         }
         int rows = p + D, g = grp0[b];
@@ -84,11 +84,11 @@ __global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mas
             const int tile = stg0 + B + b * (D - 1) + (j - 2), ns = j - 2 + D, first = r;
             for (int i = 0; i < j - 2; ++i, ++r) {
                 rm.tok[r] = yhat[i]; rm.pos[r] = n + i; rm.seq[r] = b; rm.kind[r] = i; rm.lim[r] = n;
-                rm.stg[r] = tile; rm.slim[r] = i + 1;
+                rm.stg[r] = tile; rm.smask[r] = (1 << (i + 1)) - 1;
             }
             for (int t = 0; t < D; ++t, ++r) {
                 rm.tok[r] = t == 0 ? yhat[j - 2] : mask_id; rm.pos[r] = n + j - 2 + t; rm.seq[r] = b; rm.kind[r] = j - 2 + t;
-                rm.lim[r] = n; rm.stg[r] = tile; rm.slim[r] = causal ? j - 2 + t + 1 : ns;
+                rm.lim[r] = n; rm.stg[r] = tile; rm.smask[r] = (1 << (causal ? j - 2 + t + 1 : ns)) - 1;
                 if (t == 0) rm.blk_row[b * (D - 1) + (j - 2)] = r;
             }
             for (int o = 0; o < ns; o += gr, ++g) {
@@ -392,8 +392,8 @@ void launch_rope_scatter(hipStream_t s, int dtype, const float *qkv, int n_slabs
 }
 
 // ------------------------------------------------------------------------------------------------ attention
-// One wavefront per (row, query head).  Keys: the cache positions [0, lim) of the row's sequence and the first
-// slim slots of the row's staging tile; for a block row these are the D keys of its block (mask equation, Sec. 3.3:
+// One wavefront per (row, query head).  Keys: the cache positions [0, lim) of the row's sequence and the slots of
+// the row's staging tile named by its slot mask; for a block row these are the D keys of its block (mask equation, Sec. 3.3:
 // causal below the block start, full mutual attention inside the block).  Each lane walks a strided subset of the keys with a running
 // (max, sum, output); the 64 partial results are merged at the end.
 template <typename T, int HD>
@@ -404,7 +404,8 @@ __global__ __launch_bounds__(64) void attn_generic_k(const T *q, T *out, const T
     if (r >= rm.counts[0]) return;
     const int hq = blockIdx.x, G = Hq / kg.n_kv_heads, hk = hq / G, lane = threadIdx.x;
     const int b = rm.seq[r], lim = rm.lim[r], stg = rm.stg[r];
-    const int total = lim + (stg >= 0 ? rm.slim[r] : 0);
+    const uint32_t smask = stg >= 0 ? (uint32_t)rm.smask[r] : 0u;
+    const int total = lim + (smask ? 32 - __clz(smask) : 0);   // key index lim + i stands for staging slot i
     __shared__ float qs[HD];
     __shared__ float part[64][HD + 1];
     const float scale = 1.0f / sqrtf((float)HD);
@@ -416,7 +417,7 @@ __global__ __launch_bounds__(64) void attn_generic_k(const T *q, T *out, const T
     for (int j = lane; j < total; j += 64) {
         int page, slot;
         if (j < lim) { page = st.page_table[(size_t)b * kg.pages_per_seq + j / PAGE]; slot = j % PAGE; }
-        else { page = stg; slot = j - lim; }
+        else { page = stg; slot = j - lim; if (!((smask >> slot) & 1u)) continue; }
         const T *Kb = pool + kg.tile(page, hk), *Vb = Kb + PAGE * HD;
         float sdot = 0.f;
 #pragma unroll

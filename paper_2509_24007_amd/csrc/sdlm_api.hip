@@ -380,7 +380,7 @@ int sdlm_create(const sdlm_model_cfg *m, const sdlm_run_cfg *r, void *workspace,
     int32_t *mi = (int32_t *)(ws + L.meta_i32);
     c->rm.tok = mi; mi += L.max_rows; c->rm.pos = mi; mi += L.max_rows; c->rm.seq = mi; mi += L.max_rows;
     c->rm.kind = mi; mi += L.max_rows; c->rm.lim = mi; mi += L.max_rows;
-    c->rm.stg = mi; mi += L.max_rows; c->rm.slim = mi; mi += L.max_rows;
+    c->rm.stg = mi; mi += L.max_rows; c->rm.smask = mi; mi += L.max_rows;
     c->rm.grp_row0 = mi; mi += L.max_groups; c->rm.grp_n = mi; mi += L.max_groups; c->rm.grp_seq = mi; mi += L.max_groups;
     c->rm.grp_stg = mi; mi += L.max_groups;
     c->rm.blk_row = mi; mi += (size_t)B * D;
@@ -532,7 +532,7 @@ int sdlm_prefill(sdlm_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
         int32_t counts[4] = {R, (int32_t)g0.size(), 0, 0};
         const std::vector<int32_t> none((size_t)R, -1), zero((size_t)R, 0);   // causal rows: no staging tile
         HIPCHK(c, hipMemcpyAsync(c->rm.stg, none.data(), R * 4, hipMemcpyHostToDevice, s));
-        HIPCHK(c, hipMemcpyAsync(c->rm.slim, zero.data(), R * 4, hipMemcpyHostToDevice, s));
+        HIPCHK(c, hipMemcpyAsync(c->rm.smask, zero.data(), R * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.grp_stg, none.data(), g0.size() * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.tok, tok.data(), R * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.pos, pos.data(), R * 4, hipMemcpyHostToDevice, s));
