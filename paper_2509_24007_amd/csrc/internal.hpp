@@ -103,6 +103,9 @@ struct GemmArgs {
 
 void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows,
                             int staging_base, int causal);
+// Rows one sequence contributes to a verification pass, and whether they share one staging tile (the layout for
+// block sizes whose D-2 causal rows and (D-1) D block rows fit the 16 slots of a tile) or take one tile per input.
+int verify_rows_per_seq(int D, bool *shared_tile);
 void launch_assemble_verify(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows,
                             int staging_base, int causal);
 void launch_verify_accept(hipStream_t s, const SeqState &st, const int32_t *ids_rows, int B, int D, int rule,

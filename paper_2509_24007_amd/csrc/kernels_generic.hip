@@ -56,22 +56,25 @@ void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm
 
 // Rows of the verification pass of a self-speculative step (Sec. 3.4, "Self-Speculative Decoding").  With yhat^1..yhat^D
 // the tokens of the step just computed and n the number of known tokens, verification input j (j = 2..D; input 1 is
-// the step itself) is the sequence extended by yhat^1..yhat^{j-1}.  It is laid out as a self-contained run of rows:
+// the step itself) is the sequence extended by yhat^1..yhat^{j-1}.  In the general layout (shared == 0) it is a
+// self-contained run of rows with a staging tile of its own:
 //   j-2 causal rows   yhat^1..yhat^{j-2} at positions n..n+j-3
 //   D block rows      [yhat^{j-1}, [m] x (D-1)] at positions n+j-2 ..
 // All of them see the cache keys [0, n) (written by the step: every known token including x_last has its causal K/V
 // there) and keep their own K/V in the input's staging tile: a causal row in slot i sees slots [0, i]; a block row
 // sees all j-2+D slots.  Nothing is written to the cache.  Only the first block row of each input goes through the
-// LM head: its arg-max is ytilde^j.
-__global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mask_id, int gr, int stg0, int causal)
+// LM head: its arg-max is ytilde^j.  When all rows of a sequence fit one tile (shared != 0) the causal rows are
+// computed once for all inputs; see below.
+__global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mask_id, int gr, int stg0, int causal, int shared)
 {
     __shared__ int row0[1025], grp0[1025];
-    const int rows_seq = (D - 1) * D + (D - 2) * (D - 1) / 2;
+    const int rows_seq = shared ? (D - 2) + (D - 1) * D : (D - 1) * D + (D - 2) * (D - 1) / 2;
     if (threadIdx.x == 0) {
         int g = 0;
         for (int b = 0; b < B; ++b) {
             row0[b] = b * rows_seq; grp0[b] = g;
-            for (int j = 2; j <= D; ++j) g += (j - 2 + D + gr - 1) / gr;
+            if (shared) g += (rows_seq + gr - 1) / gr;
+            else for (int j = 2; j <= D; ++j) g += (j - 2 + D + gr - 1) / gr;
         }
         rm.counts[0] = B * rows_seq; rm.counts[1] = g; rm.counts[2] = B * (D - 1); rm.counts[3] = 0;
     }
@@ -80,6 +83,33 @@ __global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mas
         const int n = st.n[b];
         const int32_t *yhat = st.last_ids + b * D;
         int r = row0[b], g = grp0[b];
+        if (shared) {
+            // One tile for the whole sequence.  The causal rows yhat^1 .. yhat^{D-2} are the same in every input that
+            // has them (same token, same position, same visible keys), so they are computed once, in slots 0 .. D-3;
+            // input j's block follows in slots D-2 + (j-2) D ..., and its rows see the causal slots 0 .. j-3 and their
+            // own block.  The rows of a sequence then form row groups regardless of the input they belong to, and the
+            // attention kernel streams the sequence's cache once per group instead of once per input.
+            const int tile = stg0 + B + b * (D - 1);
+            for (int i = 0; i < D - 2; ++i, ++r) {
+                rm.tok[r] = yhat[i]; rm.pos[r] = n + i; rm.seq[r] = b; rm.kind[r] = i; rm.lim[r] = n;
+                rm.stg[r] = tile; rm.smask[r] = (1 << (i + 1)) - 1;
+            }
+            for (int j = 2; j <= D; ++j) {
+                const int base = (D - 2) + (j - 2) * D, common = (1 << (j - 2)) - 1;
+                for (int t = 0; t < D; ++t, ++r) {
+                    rm.tok[r] = t == 0 ? yhat[j - 2] : mask_id; rm.pos[r] = n + j - 2 + t; rm.seq[r] = b; rm.kind[r] = base + t;
+                    rm.lim[r] = n; rm.stg[r] = tile; rm.smask[r] = common | (((1 << (causal ? t + 1 : D)) - 1) << base);
+                    if (t == 0) rm.blk_row[b * (D - 1) + (j - 2)] = r;
+                }
+            }
+            for (int o = 0; o < rows_seq; o += gr, ++g) {
+                rm.grp_row0[g] = row0[b] + o;
+                rm.grp_n[g] = min(gr, rows_seq - o);
+                rm.grp_seq[g] = b;
+                rm.grp_stg[g] = tile;
+            }
+            continue;
+        }
         for (int j = 2; j <= D; ++j) {
             const int tile = stg0 + B + b * (D - 1) + (j - 2), ns = j - 2 + D, first = r;
             for (int i = 0; i < j - 2; ++i, ++r) {
@@ -101,10 +131,19 @@ __global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mas
     }
 }
 
+int verify_rows_per_seq(int D, bool *shared_tile)
+{
+    const bool shared = (D - 2) + (D - 1) * D <= PAGE;   // every row of a sequence fits one staging tile
+    if (shared_tile) *shared_tile = shared;
+    return shared ? (D - 2) + (D - 1) * D : (D - 1) * D + (D - 2) * (D - 1) / 2;
+}
+
 void launch_assemble_verify(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows,
                             int staging_base, int causal)
 {
-    hipLaunchKernelGGL(assemble_verify_k, dim3(1), dim3(256), 0, s, st, rm, B, D, mask_id, group_rows, staging_base, causal);
+    bool shared;
+    verify_rows_per_seq(D, &shared);
+    hipLaunchKernelGGL(assemble_verify_k, dim3(1), dim3(256), 0, s, st, rm, B, D, mask_id, group_rows, staging_base, causal, shared ? 1 : 0);
 }
 
 // gamma_verify (Eq. 10) from the step's tokens yhat and the verification predictions (ids_rows: ytilde^2..ytilde^D per

@@ -628,10 +628,13 @@ int sdlm_verify_step(sdlm_ctx *c, int32_t rule, int32_t *ids_tilde, int32_t *cou
     if (D >= 2) {
         // positions reach n + 2D - 3 <= max_seq_len + D - 2 (decode_step checked n + D - 1 <= max_seq_len): inside the rotary
         // table; no cache slot beyond n - 1 is touched
-        const int rows = B * ((D - 1) * D + (D - 2) * (D - 1) / 2);
+        bool shared;
+        const int rows_seq = verify_rows_per_seq(D, &shared);
+        const int rows = B * rows_seq;
         const int gr = c->L.group_rows;
         int groups = 0;
-        for (int j = 2; j <= D; ++j) groups += (j - 2 + D + gr - 1) / gr;
+        if (shared) groups = (rows_seq + gr - 1) / gr;
+        else for (int j = 2; j <= D; ++j) groups += (j - 2 + D + gr - 1) / gr;
         { Phase p(c, SDLM_PH_ROWS); launch_assemble_verify(s, c->st, c->rm, B, D, c->m.mask_token_id, gr, c->kg.staging_base, c->m.block_causal); }
         run_layers(c, rows, B * groups, rows);
         run_lm_head(c, B * (D - 1), logits);

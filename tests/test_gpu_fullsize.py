@@ -302,21 +302,32 @@ def test_fullsize_verify_is_the_next_steps_first_prediction(name):
     torch.cuda.synchronize()
     ctx.tap(0, -1, None)
     yh, yt, g = yhat.cpu().numpy(), ytil.cpu().numpy(), gv.cpu().numpy()
-    # --- the verification rows: for every sequence and input j = 2..D: yhat^1..yhat^{j-2} causal, then [yhat^{j-1}, m..]
+    # --- the verification rows.  Input j = 2..D is yhat^1..yhat^{j-2} causal, then the block [yhat^{j-1}, m..].  When the
+    # D-2 distinct causal rows and the (D-1) D block rows of a sequence fit the 16 slots of one staging tile (D <= 4), the
+    # causal rows come once, first, and the blocks follow; otherwise every input is a run of its own with its own tile.
     vrows = ctx.rows()
-    rows_seq = (D - 1) * D + (D - 2) * (D - 1) // 2
+    shared = (D - 2) + (D - 1) * D <= 16
+    rows_seq = (D - 2) + (D - 1) * D if shared else (D - 1) * D + (D - 2) * (D - 1) // 2
     assert len(vrows["tok"]) == B * rows_seq
     first_row = {}
     r0 = 0
     for b in range(B):
-        for j in range(2, D + 1):
-            want_tok = [int(x) for x in yh[b, : j - 2]] + [int(yh[b, j - 2])] + [m.mask_token_id] * (D - 1)
-            want_pos = list(range(n0[b], n0[b] + j - 2)) + list(range(n0[b] + j - 2, n0[b] + j - 2 + D))
-            k = j - 2 + D
-            assert vrows["tok"][r0:r0 + k].tolist() == want_tok and vrows["pos"][r0:r0 + k].tolist() == want_pos
-            assert vrows["seq"][r0:r0 + k].eq(b).all() and vrows["kind"][r0:r0 + k].tolist() == list(range(k))
-            first_row[(b, j)] = r0 + j - 2
+        if shared:
+            k = D - 2
+            assert vrows["tok"][r0:r0 + k].tolist() == [int(x) for x in yh[b, :k]]
+            assert vrows["pos"][r0:r0 + k].tolist() == list(range(n0[b], n0[b] + k)) and vrows["kind"][r0:r0 + k].tolist() == list(range(k))
             r0 += k
+        for j in range(2, D + 1):
+            lead = 0 if shared else j - 2
+            want_tok = [int(x) for x in yh[b, :lead]] + [int(yh[b, j - 2])] + [m.mask_token_id] * (D - 1)
+            want_pos = list(range(n0[b], n0[b] + lead)) + list(range(n0[b] + j - 2, n0[b] + j - 2 + D))
+            k = lead + D
+            slot0 = (D - 2) + (j - 2) * D if shared else 0
+            assert vrows["tok"][r0:r0 + k].tolist() == want_tok and vrows["pos"][r0:r0 + k].tolist() == want_pos
+            assert vrows["kind"][r0:r0 + k].tolist() == list(range(slot0, slot0 + k))
+            first_row[(b, j)] = r0 + lead
+            r0 += k
+        assert vrows["seq"][r0 - rows_seq:r0].eq(b).all()
     assert np.array_equal(yt[:, 0], yh[:, 0])
     for b in range(B):
         assert int(g[b]) == orc.gamma_verify(yh[b], yt[b], 0)

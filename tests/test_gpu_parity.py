@@ -269,10 +269,11 @@ def test_bf16_mfma_entropy_confidence():
 
 
 # ------------------------------------------------------------------ self-speculative verification (Sec. 3.4, Eq. 10)
-@pytest.mark.parametrize("D,rule,paged", [(2, 0, False), (4, 0, True), (4, 1, False), (6, 0, True), (9, 1, False)])
+@pytest.mark.parametrize("D,rule,paged", [(2, 0, False), (3, 1, True), (4, 0, True), (4, 1, False), (5, 0, False), (6, 0, True), (9, 1, False)])
 def test_verify_small_fp32(D, rule, paged):
     """Second pass of a self-speculative step against the oracle's: logits of every verification input, ytilde,
-    gamma_verify bit-exact, and the verified count is what an argument-less commit publishes."""
+    gamma_verify bit-exact, and the verified count is what an argument-less commit publishes.  D <= 4: the rows of a
+    sequence share one staging tile and its causal rows are computed once; D >= 5: one tile per input."""
     m = gpu_cfg()
     om, g_dev, layers_dev = both_models(m, seed=6, std=0.3)
     lens = [1, 2, 15, 16, 17, 33]
@@ -369,6 +370,9 @@ def test_verify_error_paths():
     ("vg2", {}, [1, 9, 40, 100], 4),
     ("vg7", dict(n_q_heads=14, n_kv_heads=2, vocab=1000, ffn=320), [3, 17, 33, 64, 70], 4),
     ("vg8-D8-two-groups-per-input", dict(n_q_heads=16, n_kv_heads=2, hidden=512), [5, 130, 300], 8),
+    ("vg16-four-groups-across-inputs", dict(n_q_heads=16, n_kv_heads=1, hidden=256), [2, 31, 90], 4),
+    ("vg4-D3", dict(n_q_heads=8, n_kv_heads=2), [7, 16, 49], 3),
+    ("vg3-D5-tile-per-input", dict(n_q_heads=6, n_kv_heads=2), [4, 40], 5),
 ])
 def test_verify_bf16_mfma(name, kw, lens, D):
     m = mfma_cfg(**kw)
