@@ -302,3 +302,51 @@ def test_probes_match_forward_pieces():
     Wb = torch.tensor(W).to(torch.bfloat16)
     Wb_np = Wb.view(torch.int16).numpy().view(np.uint16)
     assert abs(orc.probe_linear(Wb_np, None, x, 3) - (Wb.to(torch.float64).numpy()[3] @ x)) < 1e-12
+
+
+def test_lm_head_probes_hand_case_and_scale():
+    """The full-size LM-head reference (one logit, one row of logits): z_v = logit_scale * <xhat, W_lm[v]>
+    (logits Z, Sec. 3.2; the scale is a configuration constant of the synthetic workloads).  Hand case: a one-hot
+    xhat picks one column of W_lm; the scale multiplies it; rows and columns of W_lm are not interchangeable
+    (V != h)."""
+    m = small_cfg(vocab=11, hidden=8, ffn=16, n_q_heads=2, n_kv_heads=1, head_dim=4, logit_scale=3.0)
+    g, layers = make_model(m, seed=5, std=0.5)
+    model = oracle_model(m, g, layers)
+    W = g["lm_head"].numpy().astype(np.float64)               # [V, h]
+    for k in (0, 5, 7):
+        e = np.zeros(m.hidden)
+        e[k] = 1.0
+        row = orc.probe_logits_row(model, e)
+        np.testing.assert_allclose(row, 3.0 * W[:, k], rtol=1e-14)
+        for v in (0, 4, 10):
+            assert abs(orc.probe_logit(model, e, v) - 3.0 * W[v, k]) < 1e-14
+    # linear in xhat; the scale is applied once
+    x = np.random.default_rng(3).standard_normal(m.hidden)
+    row = orc.probe_logits_row(model, x)
+    np.testing.assert_allclose(row, 3.0 * (W @ x), rtol=1e-13)
+    np.testing.assert_allclose([orc.probe_logit(model, x, v) for v in range(m.vocab)], row, rtol=1e-13)
+    m1 = small_cfg(vocab=11, hidden=8, ffn=16, n_q_heads=2, n_kv_heads=1, head_dim=4, logit_scale=1.0)
+    np.testing.assert_allclose(orc.probe_logits_row(oracle_model(m1, g, layers), x) * 3.0, row, rtol=1e-13)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_lm_head_probes_match_the_forward(dtype):
+    """With zero output and down projections the residual stream that reaches the final norm is the embedding of
+    the row's token, so the forward's logits (pinned above to the library decoder) must equal the probe applied to
+    the normalised embedding, the normalisation written out here from its definition."""
+    m = small_cfg(dtype=dtype, vocab=53, hidden=24, n_q_heads=4, n_kv_heads=2, head_dim=6, ffn=40, logit_scale=8.0)
+    g, layers = make_model(m, seed=11, std=0.3)
+    for L in layers:
+        L["wo"] = torch.zeros_like(L["wo"])
+        L["w_down"] = torch.zeros_like(L["w_down"])
+    model = oracle_model(m, g, layers)
+    ids = syn.uniform_int(4, "t", 6, 0, m.vocab - 1).numpy()
+    causal = np.tril(np.ones((6, 6), np.uint8))
+    Z = orc.forward_masked_logits(model, ids, causal, 0, 6)
+    E = g["embed"].to(torch.float64).numpy()
+    for r in range(6):
+        x = E[ids[r]]
+        xhat = x / math.sqrt(float(np.mean(x * x)) + m.rms_eps) * g["final_norm"].to(torch.float64).numpy()
+        assert rel_err(orc.probe_logits_row(model, xhat), Z[r]) < 1e-13
+        for v in (0, 17, 52):
+            assert abs(orc.probe_logit(model, xhat, v) - Z[r, v]) <= 1e-12 * np.max(np.abs(Z[r]))
