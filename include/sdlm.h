@@ -67,7 +67,8 @@ typedef struct {
 
 typedef struct {
     int32_t max_batch;   /* sequences decoded together, >= 1 */
-    int32_t max_seq_len; /* positions a sequence may occupy, block rows included */
+    int32_t max_seq_len; /* most known tokens a sequence may reach; a step needs n_b + D <= max_seq_len, so that
+                            accepting all D tokens still fits */
     int32_t block_D;     /* D: block size, 1..16 */
     int32_t kv_layout;   /* 0: contiguous (each sequence owns a fixed run of 16-token tiles sized for
                             max_seq_len); 1: paged (tiles handed out from a shared pool on demand) */
@@ -119,7 +120,7 @@ int sdlm_init_weights(sdlm_ctx *ctx, const sdlm_weights *w, int32_t on_device);
  * Start `batch` sequences (1..max_batch) from their prompts and fill the cache with a causal forward over
  * each prompt (no block rows, no LM head).  ids_packed [host]: all prompts back to back; offsets [host]:
  * batch+1 entries, prompt b is ids_packed[offsets[b] .. offsets[b+1]).  Every prompt needs >= 1 token and
- * len + D - 1 <= max_seq_len.  Discards all earlier sequences.  Afterwards n_b = c_b = len_b.
+ * len + D <= max_seq_len.  Discards all earlier sequences.  Afterwards n_b = c_b = len_b.
  */
 int sdlm_prefill(sdlm_ctx *ctx, int32_t batch, const int32_t *ids_packed, const int32_t *offsets);
 
@@ -133,8 +134,9 @@ int sdlm_prefill(sdlm_ctx *ctx, int32_t batch, const int32_t *ids_packed, const 
  *   logits [batch*D,V] float  the logits Z (may be NULL; costs a batch*D*V write).
  * The step publishes nothing: K/V of the pending tokens are written into cache slots that stay invisible
  * until sdlm_kv_commit, and the block rows' K/V live in per-step staging.  It may therefore be repeated.
- * Errors: SDLM_ESTATE before prefill; SDLM_ECAPACITY if a sequence could exceed max_seq_len (the host tracks
- * an upper bound of each length and refreshes it with a stream synchronisation only when the bound trips).
+ * Errors: SDLM_ESTATE before prefill; SDLM_ECAPACITY if n_b + D > max_seq_len for some sequence, i.e. if accepting
+ * all D tokens would not fit (the host tracks an upper bound of each length and refreshes it with a stream
+ * synchronisation only when the bound trips; the same refresh reports a page pool that ran out at the last commit).
  */
 int sdlm_decode_step(sdlm_ctx *ctx, int32_t *ids, int32_t *count, float *conf, float *logits);
 

@@ -481,7 +481,7 @@ int sdlm_prefill(sdlm_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
     for (int b = 0; b < batch; ++b) {
         int len = offsets[b + 1] - offsets[b];
         if (len < 1) return fail(c, SDLM_EINVAL, "prompt %d is empty", b);
-        if (len + D - 1 > c->r.max_seq_len) return fail(c, SDLM_ECAPACITY, "prompt %d: %d tokens + block exceed max_seq_len %d", b, len, c->r.max_seq_len);
+        if (len + D > c->r.max_seq_len) return fail(c, SDLM_ECAPACITY, "prompt %d: %d tokens + a block of %d exceed max_seq_len %d", b, len, D, c->r.max_seq_len);
         for (int i = offsets[b]; i < offsets[b + 1]; ++i)
             if (ids[i] < 0 || ids[i] >= c->m.vocab) return fail(c, SDLM_EINVAL, "token id %d outside the vocabulary", ids[i]);
         pages_needed += (len + PAGE - 1) / PAGE;
@@ -567,14 +567,18 @@ int sdlm_decode_step(sdlm_ctx *c, int32_t *ids, int32_t *count, float *conf, flo
     if (!c->prefilled) return fail(c, SDLM_ESTATE, "decode_step before prefill");
     if (!ids || !count) return fail(c, SDLM_EINVAL, "ids and count outputs are required");
     const int B = c->batch, D = c->r.block_D;
+    // A step may accept all D tokens, and the commit must then be able to hold n + D known tokens: the step is refused
+    // unless n + D <= max_seq_len, so that no commit can run out of positions (or of page-table entries) on the device.
     bool tight = false;
-    for (int b = 0; b < B; ++b) tight |= c->n_ub[b] + D - 1 > c->r.max_seq_len;
+    for (int b = 0; b < B; ++b) tight |= c->n_ub[b] + D > c->r.max_seq_len;
     if (tight) {
-        int rc = refresh_lengths(c, nullptr);
+        int32_t flags = 0;
+        int rc = refresh_lengths(c, &flags);
         if (rc) return rc;
+        if (flags & 1) return fail(c, SDLM_ECAPACITY, "a sequence could not grow at the last commit: page pool exhausted");
         for (int b = 0; b < B; ++b)
-            if (c->n_ub[b] + D - 1 > c->r.max_seq_len)
-                return fail(c, SDLM_ECAPACITY, "sequence %d: %d tokens + block exceed max_seq_len %d", b, c->n_ub[b], c->r.max_seq_len);
+            if (c->n_ub[b] + D > c->r.max_seq_len)
+                return fail(c, SDLM_ECAPACITY, "sequence %d: %d tokens + a block of %d exceed max_seq_len %d", b, c->n_ub[b], D, c->r.max_seq_len);
     }
     hipStream_t s = c->stream;
     auto launch_all = [&]() {
@@ -626,7 +630,7 @@ int sdlm_verify_step(sdlm_ctx *c, int32_t rule, int32_t *ids_tilde, int32_t *cou
     if (2 * D - 2 > PAGE) return fail(c, SDLM_EINVAL, "verification needs 2D-2 <= %d staging slots; block_D is %d", PAGE, D);
     hipStream_t s = c->stream;
     if (D >= 2) {
-        // positions reach n + 2D - 3 <= max_seq_len + D - 2 (decode_step checked n + D - 1 <= max_seq_len): inside the rotary
+        // positions reach n + 2D - 3 <= max_seq_len + D - 3 (decode_step checked n + D <= max_seq_len): inside the rotary
         // table; no cache slot beyond n - 1 is touched
         bool shared;
         const int rows_seq = verify_rows_per_seq(D, &shared);

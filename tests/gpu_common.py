@@ -22,71 +22,94 @@ def gpu_context(mcfg, g_dev, layers_dev, *, max_batch, max_seq_len, D, tau, page
     return ctx
 
 
-def both_models(mcfg, seed, std, rounded=False):
-    """Weights generated once on the CPU (for the oracle) and moved to the GPU unchanged.
-
-    rounded=True returns (oracle with the bf16 rounding-point model, exact oracle) in place of the exact oracle."""
+def both_models(mcfg, seed, std):
+    """Weights generated once on the CPU (for the oracle) and moved to the GPU unchanged."""
     g, layers = make_model(mcfg, seed=seed, std=std)
     om = oracle_model(mcfg, g, layers)
-    if rounded:
-        om = (orc.model_from_inputs(mcfg, g, layers, bf16_points=True), om)
     g_dev = {k: v.cuda() for k, v in g.items()}
     layers_dev = [{k: (v.cuda() if v is not None else None) for k, v in L.items()} for L in layers]
     return om, g_dev, layers_dev
 
 
+TIE_GAP = 1e-3          # the stated band: top-2 logit gap, |confidence product - tau|
+FLIP_CEILING = 0.10     # most rows / sequences-steps of a bf16 run whose decision may differ outside that band
+
+
 class Stats:
     def __init__(self):
-        self.rows = self.id_near_tie = self.gamma_near_tie = 0
-        self.max_logit_err = self.max_conf_err = 0.0
+        self.rows = self.seq_steps = 0
+        self.id_near_tie = self.gamma_near_tie = 0      # decisions that differ inside the stated 1e-3 bands
+        self.id_flip_bf16 = self.gamma_flip_bf16 = 0    # bf16 only: outside the band, within the row's own measured error
+        self.max_logit_err = self.max_conf_err = self.max_logconf_err = 0.0
         self.gammas = []
-        self.exact_errs = []
         self.row_errs = []
+        self.model_errs = []                            # rounding-model oracle vs exact oracle, same rows (if requested)
+        self.model_id_flips = self.model_gamma_flips = 0    # ... and how many of its decisions differ outside the band
 
     def __repr__(self):
         return (f"rows={self.rows} max_logit_rel_err={self.max_logit_err:.3e} max_conf_err={self.max_conf_err:.3e} "
                 + (f"median_logit_rel_err={np.median(self.row_errs):.3e} p90={np.quantile(self.row_errs, 0.9):.3e} " if self.row_errs else "") +
-                f"id_near_tie={self.id_near_tie} gamma_near_tie={self.gamma_near_tie} mean_gamma={np.mean(self.gammas):.2f}"
-                + (f" vs_exact_oracle[max={np.max(self.exact_errs):.3e} median={np.median(self.exact_errs):.3e} "
-                   f"p90={np.quantile(self.exact_errs, 0.9):.3e}]" if self.exact_errs else ""))
+                f"id_near_tie={self.id_near_tie} gamma_near_tie={self.gamma_near_tie} id_flip_bf16={self.id_flip_bf16} "
+                f"gamma_flip_bf16={self.gamma_flip_bf16} mean_gamma={np.mean(self.gammas):.2f}"
+                + (f" ideal_bf16_pipeline_vs_exact[max={np.max(self.model_errs):.3e} median={np.median(self.model_errs):.3e} "
+                   f"p90={np.quantile(self.model_errs, 0.9):.3e} id_flips={self.model_id_flips} gamma_flips={self.model_gamma_flips}]"
+                   if self.model_errs else ""))
 
 
 def lockstep(ctx, om, prompts, D, tau, steps, *, logit_tol, conf_tol, conf_fn=0, rule=0, overrides=None,
-             tie_gap=1e-3, bf16=False, check_logits=True, max_len=None, om_exact=None, exact_tol=2e-2, verify_rule=None):
+             bf16=False, max_len=None, verify_rule=None, oracle_seqs=None, flip_ceiling=FLIP_CEILING, floor_model=None):
     """Run the HIP library and one oracle sequence per prompt step by step on the same token history.
 
     After every step both sides commit the same tokens: the seeded override tokens on steps where `overrides`
     supplies them, otherwise the oracle's own accepted prefix (through the library's NULL commit when the two
-    agree, through the override arguments otherwise).  Returns Stats; asserts the parity bar.
+    agree, through the override arguments otherwise).  Returns Stats; asserts the parity bar:
+
+      logits       row-normalised max error <= logit_tol, every block row;
+      ids, gamma   bit-exact, except where the oracle's top-2 logit gap (ids) or |product of confidences - tau|
+                   (gamma) is below 1e-3: those are counted as near ties.  In bf16 a decision may also differ
+                   outside that band when the row's own measured logit error (the sequence-step's own measured
+                   deviation of the confidence products) covers the gap; such flips are counted separately and
+                   their number is bounded by `flip_ceiling` (a fraction of the rows checked);
+      confidence   fp32: |difference| <= conf_tol.  bf16: the library's confidence is a function of its own
+                   logits, which differ from the oracle's by the measured e = max_v |z - z_ref| of that row; the
+                   softmax probability of the arg-max then moves by a factor within exp(+-2e) and the normalised
+                   entropy by at most 2e, so the check is |log conf - log conf_ref| <= 2e (+ conf_tol), resp.
+                   |conf - conf_ref| <= 2e + conf_tol, with the measured e, not the tolerance.
 
     With `verify_rule` (0 or 1) every step is a self-speculative one: after the step the library's verification pass
     runs and is compared with the oracle's (logits of every verification input, ytilde, gamma_verify), and the
     verified count is what gets committed.
 
-    `om` may be the oracle with the bf16 rounding-point model switched on; `om_exact`, if given, is the plain
-    fp64 oracle run alongside on the same tokens: the library's logits must also stay within `exact_tol`
-    (row-normalised) of it.
+    `oracle_seqs`: indices of the prompts the oracle follows (default: all).  The library always runs the whole
+    batch; sequences the oracle does not follow are committed with the library's own result.
+
+    `floor_model`: the oracle with its bf16 rounding-point model switched on (same weights).  It follows the same
+    sequences on the same tokens, and its row-normalised distance from the exact oracle is recorded per row in
+    Stats.model_errs: what an ideal bf16 pipeline (exact accumulation, rounding only where bf16 contractions and a
+    bf16 cache force it) loses on these rows.
     """
     B = len(prompts)
     V = om.vocab
     max_len = max_len or max(len(p) for p in prompts) + steps * D + D
-    seqs = [orc.Seq(om, max_len) for _ in range(B)]
-    for s, p in zip(seqs, prompts):
-        s.prefill(np.asarray(p))
-    seqs_x = [orc.Seq(om_exact, max_len) for _ in range(B)] if om_exact is not None else []
-    for s, p in zip(seqs_x, prompts):
-        s.prefill(np.asarray(p))
+    followed = list(range(B)) if oracle_seqs is None else sorted(oracle_seqs)
+    seqs = {b: orc.Seq(om, max_len) for b in followed}
+    for b in followed:
+        seqs[b].prefill(np.asarray(prompts[b]))
+    seqs_m = {b: orc.Seq(floor_model, max_len) for b in followed} if floor_model is not None else {}
+    for b in seqs_m:
+        seqs_m[b].prefill(np.asarray(prompts[b]))
     ctx.prefill(prompts)
     ids = torch.empty(B, D, dtype=torch.int32, device="cuda")
     cnt = torch.empty(B, dtype=torch.int32, device="cuda")
     conf = torch.empty(B, D, dtype=torch.float32, device="cuda")
-    logits = torch.empty(B * D, V, dtype=torch.float32, device="cuda") if check_logits else None
+    logits = torch.empty(B * D, V, dtype=torch.float32, device="cuda")
     st = Stats()
     if verify_rule is not None:
+        assert oracle_seqs is None
         v_ids = torch.empty(B, D, dtype=torch.int32, device="cuda")
         v_cnt = torch.empty(B, dtype=torch.int32, device="cuda")
         v_log = torch.empty(B, max(D - 1, 1), V, dtype=torch.float32, device="cuda")
-        st.verify_rows = st.verify_skipped = st.verify_near_tie = 0
+        st.verify_rows = st.verify_skipped = st.verify_near_tie = st.verify_flip_bf16 = 0
         st.verify_gammas = []
     for t in range(steps):
         ctx.decode_step(ids, cnt, conf, logits)
@@ -95,50 +118,60 @@ def lockstep(ctx, om, prompts, D, tau, steps, *, logit_tol, conf_tol, conf_fn=0,
             ctx.verify_step(verify_rule, v_ids, v_cnt, v_log)
         torch.cuda.synchronize()
         g_ids, g_cnt, g_conf = ids.cpu().numpy(), cnt.cpu().numpy(), conf.cpu().numpy()
-        g_log = logits.cpu().numpy().reshape(B, D, V) if check_logits else None
         agree = True
-        o_ids = np.zeros((B, D), np.int32)
-        o_cnt = np.zeros(B, np.int32)
-        for b in range(B):
+        o_ids, o_cnt = g_ids.copy(), g_cnt.copy()       # sequences the oracle does not follow keep the library's result
+        for b in followed:
+            g_log = logits[b * D:(b + 1) * D].cpu().numpy()
             lo, io, co, go = seqs[b].step(D, tau, rule, conf_fn)
             o_ids[b], o_cnt[b] = io, go
+            st.seq_steps += 1
             for k in range(D):
                 st.rows += 1
                 srt = np.sort(lo[k])
                 gap, zmax = srt[-1] - srt[-2], np.max(np.abs(lo[k]))
-                err_abs = 0.0
-                if check_logits:
-                    err_abs = float(np.max(np.abs(g_log[b, k] - lo[k])))
-                    st.max_logit_err = max(st.max_logit_err, err_abs / zmax)
-                    st.row_errs.append(err_abs / zmax)
-                    assert err_abs / zmax <= logit_tol, f"step {t} seq {b} row {k}: logit rel err {err_abs / zmax:.3e}"
-                band = max(tie_gap, 2.0 * err_abs) if bf16 else tie_gap
+                err_abs = float(np.max(np.abs(g_log[k] - lo[k])))
+                st.max_logit_err = max(st.max_logit_err, err_abs / zmax)
+                st.row_errs.append(err_abs / zmax)
+                assert err_abs / zmax <= logit_tol, f"step {t} seq {b} row {k}: logit rel err {err_abs / zmax:.3e}"
                 if g_ids[b, k] != io[k]:
-                    assert gap < band, f"step {t} seq {b} row {k}: id {g_ids[b, k]} vs {io[k]}, top-2 gap {gap:.3e}, band {band:.3e}"
-                    st.id_near_tie += 1
                     agree = False
-                # a logit perturbation of at most delta moves the softmax probability by a factor within
-                # exp(+-2 delta), and the normalised entropy by at most 2 delta (sum_v |p_v (log p_v + H)| <= 2 log V)
-                delta = logit_tol * zmax
-                allowed = max(conf_tol, float(co[k]) * (np.exp(2 * delta) - 1) if conf_fn == 0 else 2 * delta)
-                cerr = abs(float(g_conf[b, k]) - float(co[k]))
-                st.max_conf_err = max(st.max_conf_err, cerr)
-                assert cerr <= allowed, f"step {t} seq {b} row {k}: conf {g_conf[b, k]} vs {co[k]} (allowed {allowed:.2e})"
+                    if gap < TIE_GAP:
+                        st.id_near_tie += 1
+                    else:
+                        assert bf16 and gap <= 2.0 * err_abs, \
+                            f"step {t} seq {b} row {k}: id {g_ids[b, k]} vs {io[k]}, top-2 gap {gap:.3e}, logit error {err_abs:.3e}"
+                        st.id_flip_bf16 += 1
+                cg, cr = float(g_conf[b, k]), float(co[k])
+                st.max_conf_err = max(st.max_conf_err, abs(cg - cr))
+                if not bf16:
+                    assert abs(cg - cr) <= conf_tol, f"step {t} seq {b} row {k}: conf {cg} vs {cr}"
+                elif conf_fn == 0:
+                    lerr = abs(np.log(max(cg, 1e-300)) - np.log(max(cr, 1e-300)))
+                    st.max_logconf_err = max(st.max_logconf_err, lerr)
+                    assert lerr <= 2.0 * err_abs + conf_tol, f"step {t} seq {b} row {k}: conf {cg} vs {cr}, logit error {err_abs:.3e}"
+                else:
+                    assert abs(cg - cr) <= 2.0 * err_abs + conf_tol, f"step {t} seq {b} row {k}: conf {cg} vs {cr}, logit error {err_abs:.3e}"
             # the library's own gamma is the acceptance rule applied to its own confidences, bit for bit
             assert int(g_cnt[b]) == orc.gamma(g_conf[b], tau, rule)
             if int(g_cnt[b]) != go:
-                prods = np.cumprod(co.astype(np.float32)) if rule == 0 else co
-                assert np.min(np.abs(prods - np.float32(tau))) < max(1e-3, 2 * D * st.max_conf_err), \
-                    f"step {t} seq {b}: gamma {g_cnt[b]} vs {go}, conf {co}"
-                st.gamma_near_tie += 1
                 agree = False
+                po = np.cumprod(co.astype(np.float32)) if rule == 0 else co
+                pg = np.cumprod(g_conf[b].astype(np.float32)) if rule == 0 else g_conf[b]
+                dist = float(np.min(np.abs(po - np.float32(tau))))
+                if dist < TIE_GAP:
+                    st.gamma_near_tie += 1
+                else:
+                    assert bf16 and dist <= float(np.max(np.abs(pg - po))), f"step {t} seq {b}: gamma {g_cnt[b]} vs {go}, conf {co} vs {g_conf[b]}"
+                    st.gamma_flip_bf16 += 1
             st.gammas.append(go)
-            if seqs_x and check_logits:
-                lx, _, _, _ = seqs_x[b].step(D, tau, rule, conf_fn)
+            if seqs_m:
+                lm, im, cm, gm = seqs_m[b].step(D, tau, rule, conf_fn)
+                st.model_errs += [float(np.max(np.abs(lm[k] - lo[k])) / np.max(np.abs(lo[k]))) for k in range(D)]
                 for k in range(D):
-                    e = float(np.max(np.abs(g_log[b, k] - lx[k])) / np.max(np.abs(lx[k])))
-                    st.exact_errs.append(e)
-                    assert e <= exact_tol, f"step {t} seq {b} row {k}: {e:.3e} from the exact oracle (> {exact_tol})"
+                    srt = np.sort(lo[k])
+                    st.model_id_flips += int(im[k] != io[k] and srt[-1] - srt[-2] >= TIE_GAP)
+                po = np.cumprod(co.astype(np.float32)) if rule == 0 else co
+                st.model_gamma_flips += int(gm != go and float(np.min(np.abs(po - np.float32(tau)))) >= TIE_GAP)
         if verify_rule is not None:
             gv_ids, gv_cnt, gv_log = v_ids.cpu().numpy(), v_cnt.cpu().numpy(), v_log.cpu().numpy()
             for b in range(B):
@@ -161,10 +194,12 @@ def lockstep(ctx, om, prompts, D, tau, steps, *, logit_tol, conf_tol, conf_fn=0,
                     assert err_abs / zmax <= logit_tol, f"step {t} seq {b} verify input {j}: logit rel err {err_abs / zmax:.3e}"
                     if gv_ids[b, j - 1] != yt[j - 1]:
                         srt = np.sort(zo)
-                        band = max(tie_gap, 2.0 * err_abs) if bf16 else tie_gap
-                        assert srt[-1] - srt[-2] < band, f"step {t} seq {b} verify input {j}: id {gv_ids[b, j - 1]} vs {yt[j - 1]}"
-                        st.verify_near_tie += 1
                         agree = False
+                        if srt[-1] - srt[-2] < TIE_GAP:
+                            st.verify_near_tie += 1
+                        else:
+                            assert bf16 and srt[-1] - srt[-2] <= 2.0 * err_abs, f"step {t} seq {b} verify input {j}: id {gv_ids[b, j - 1]} vs {yt[j - 1]}"
+                            st.verify_flip_bf16 += 1
                 if np.array_equal(gv_ids[b], yt):
                     assert int(gv_cnt[b]) == gv
         if overrides is not None and t < overrides[0].shape[0] and t % 2 == 1:
@@ -177,10 +212,18 @@ def lockstep(ctx, om, prompts, D, tau, steps, *, logit_tol, conf_tol, conf_fn=0,
             ctx.kv_commit()
         else:
             ctx.kv_commit(torch.tensor(c_ids, dtype=torch.int32).cuda().contiguous(), torch.tensor(c_cnt, dtype=torch.int32).cuda())
-        for b in range(B):
+        for b in followed:
             assert seqs[b].commit(c_ids[b], int(c_cnt[b])) == 0
-            if seqs_x:
-                assert seqs_x[b].commit(c_ids[b], int(c_cnt[b])) == 0
+            if seqs_m:
+                assert seqs_m[b].commit(c_ids[b], int(c_cnt[b])) == 0
         n, c = ctx.get_lengths()
-        assert [int(v) for v in n] == [s.n for s in seqs] and [int(v) for v in c] == [s.c for s in seqs]
-    return st, seqs
+        assert [int(n[b]) for b in followed] == [seqs[b].n for b in followed]
+        assert [int(c[b]) for b in followed] == [seqs[b].c for b in followed]
+    # Decisions that differ outside the stated bands are bf16 rounding at work; they must stay rare: at most
+    # flip_ceiling of the rows, or, when the ideal bf16 pipeline is followed as well, at most 1.5 x (+2) what it flips
+    # on the same rows (deep random-weight models amplify the rounding until a fifth of the arg-maxima move).
+    id_cap = max(flip_ceiling * st.rows, 1.5 * st.model_id_flips + 2 if seqs_m else 0)
+    g_cap = max(1.0, flip_ceiling * st.seq_steps, 1.5 * st.model_gamma_flips + 2 if seqs_m else 0)
+    assert st.id_flip_bf16 <= id_cap, f"{st.id_flip_bf16} of {st.rows} ids differ outside the 1e-3 band (cap {id_cap:.1f}): {st}"
+    assert st.gamma_flip_bf16 <= g_cap, f"{st.gamma_flip_bf16} of {st.seq_steps} gammas differ outside the 1e-3 band (cap {g_cap:.1f}): {st}"
+    return st, [seqs[b] for b in followed]

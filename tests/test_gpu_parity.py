@@ -146,7 +146,7 @@ def test_error_paths():
         ctx.prefill([[1, 2, 3], []])
     assert e.value.code == sdlm.EINVAL
     with pytest.raises(sdlm.SdlmError) as e:
-        ctx.prefill([list(range(22))])                      # 22 + D - 1 > 24
+        ctx.prefill([list(range(21))])                      # 21 + D > 24
     assert e.value.code == sdlm.ECAPACITY
     with pytest.raises(sdlm.SdlmError) as e:
         ctx.prefill([[1, 2, m.vocab]])
@@ -163,7 +163,7 @@ def test_error_paths():
             ctx.kv_commit(toks, four)
     assert e.value.code == sdlm.ECAPACITY
     n, c = ctx.get_lengths()
-    assert int(n.max()) + 4 - 1 > 24 and int(n.max()) <= 24
+    assert int(n.max()) + 4 > 24 and int(n.max()) <= 24
     # a clamped override count is reported
     ctx.prefill([[1, 2, 3]])
     ctx.decode_step(ids, cnt)
@@ -193,6 +193,56 @@ def test_error_paths():
             ctx.decode_step(ids, cnt)
             ctx.kv_commit(toks, four)
     assert e.value.code == sdlm.ECAPACITY
+    ctx.close()
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_commit_at_the_capacity_edge(paged):
+    """A step is admitted only if accepting all D tokens still fits (n + D <= max_seq_len), so a commit can never run
+    out of positions or page-table entries on the device: with max_seq_len a multiple of the page size, a sequence
+    that fills up exactly keeps every accepted token, reports no error, and the next step is refused on the host."""
+    from paper_2509_24007_amd import sdlm
+    m = gpu_cfg()
+    om, g_dev, layers_dev = both_models(m, seed=13, std=0.3)
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=2, max_seq_len=64, D=4, tau=0.5, paged=paged, n_pages=8 if paged else 0)
+    with pytest.raises(sdlm.SdlmError) as e:
+        ctx.prefill([list(range(61)), [1, 2]])              # 61 + 4 > 64: all four tokens could not be kept
+    assert e.value.code == sdlm.ECAPACITY
+    prompts = [syn.uniform_int(13, "edge", 60, 0, m.vocab - 1).numpy(), np.array([3, 4], np.int32)]
+    seqs = [orc.Seq(om, 64) for _ in prompts]
+    for s, p in zip(seqs, prompts):
+        s.prefill(p)
+    ctx.prefill(prompts)
+    ids = torch.empty(2, 4, dtype=torch.int32, device="cuda")
+    cnt = torch.empty(2, dtype=torch.int32, device="cuda")
+    logits = torch.empty(8, m.vocab, dtype=torch.float32, device="cuda")
+    ctx.decode_step(ids, cnt, None, logits)
+    toks = torch.tensor([[5, 6, 7, 8], [9, 10, 11, 12]], dtype=torch.int32, device="cuda")
+    ctx.kv_commit(toks, torch.tensor([4, 1], dtype=torch.int32, device="cuda"))
+    n, c = ctx.get_lengths()                                # no device-side error flag
+    assert n.tolist() == [64, 3] and c.tolist() == [60, 2]
+    with pytest.raises(sdlm.SdlmError) as e:
+        ctx.decode_step(ids, cnt)                           # 64 + 4 > 64
+    assert e.value.code == sdlm.ECAPACITY
+    ctx.close()
+    # the same two sequences with room for one more step: the four committed tokens are really there (the step after
+    # the commit matches the oracle, which was fed the same tokens)
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=2, max_seq_len=80, D=4, tau=0.5, paged=paged, n_pages=10 if paged else 0)
+    seqs = [orc.Seq(om, 80) for _ in prompts]
+    for s, p in zip(seqs, prompts):
+        s.prefill(p)
+    ctx.prefill(prompts)
+    ctx.decode_step(ids, cnt)
+    for s in seqs:
+        s.step(4, 0.5)
+    ctx.kv_commit(toks, torch.tensor([4, 1], dtype=torch.int32, device="cuda"))
+    assert seqs[0].commit([5, 6, 7, 8], 4) == 0 and seqs[1].commit([9], 1) == 0
+    ctx.decode_step(ids, cnt, None, logits)
+    torch.cuda.synchronize()
+    z = logits.cpu().numpy().reshape(2, 4, -1)
+    for b in range(2):
+        lo, io, _, _ = seqs[b].step(4, 0.5)
+        assert np.max(np.abs(z[b] - lo)) <= 1e-4 * np.max(np.abs(lo))
     ctx.close()
 
 
