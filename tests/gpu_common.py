@@ -70,7 +70,7 @@ def lockstep(ctx, om, prompts, D, tau, steps, *, logit_tol, conf_tol, conf_fn=0,
                    outside that band when the row's own measured logit error (the sequence-step's own measured
                    deviation of the confidence products) covers the gap; such flips are counted separately and
                    their number is bounded by `flip_ceiling` (a fraction of the rows checked);
-      confidence   fp32: |difference| <= conf_tol.  bf16: the library's confidence is a function of its own
+      confidence   the library's confidence is a function of its own
                    logits, which differ from the oracle's by the measured e = max_v |z - z_ref| of that row; the
                    softmax probability of the arg-max then moves by a factor within exp(+-2e) and the normalised
                    entropy by at most 2e, so the check is |log conf - log conf_ref| <= 2e (+ conf_tol), resp.
@@ -143,9 +143,7 @@ def lockstep(ctx, om, prompts, D, tau, steps, *, logit_tol, conf_tol, conf_fn=0,
                         st.id_flip_bf16 += 1
                 cg, cr = float(g_conf[b, k]), float(co[k])
                 st.max_conf_err = max(st.max_conf_err, abs(cg - cr))
-                if not bf16:
-                    assert abs(cg - cr) <= conf_tol, f"step {t} seq {b} row {k}: conf {cg} vs {cr}"
-                elif conf_fn == 0:
+                if conf_fn == 0:
                     lerr = abs(np.log(max(cg, 1e-300)) - np.log(max(cr, 1e-300)))
                     st.max_logconf_err = max(st.max_logconf_err, lerr)
                     assert lerr <= 2.0 * err_abs + conf_tol, f"step {t} seq {b} row {k}: conf {cg} vs {cr}, logit error {err_abs:.3e}"
