@@ -141,6 +141,22 @@ int sdlm_prefill(sdlm_ctx *ctx, int32_t batch, const int32_t *ids_packed, const 
 int sdlm_decode_step(sdlm_ctx *ctx, int32_t *ids, int32_t *count, float *conf, float *logits);
 
 /*
+ * sdlm_decode_step for callers that cannot allocate device memory for the step's partial results: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, outputs and errors as
+ * sdlm_decode_step; the partial-result scratch of the step's kernels (split-k slabs of the projections, split-KV
+ * partial results of the attention, per-vocabulary-block partials of the LM head; in fp32 mode the logits when
+ * `logits` is NULL) lives in a 32 MiB array that is part of the library's code object instead of the workspace:
+ * 16 MiB of slabs, 12 MiB of attention partials (both only bound how far the work is split, so a large model runs
+ * with fewer splits) and 4 MiB for the LM head, which must hold batch x D rows: otherwise SDLM_ECAPACITY.  Calls
+ * no hipMalloc / hipFree and creates no events or graphs (phase timing and graph replay do not apply to it).
+ * Every GPU the library runs on holds one copy of the array until the process ends, and every context on that GPU
+ * shares it: calls that overlap on one GPU (other streams, other contexts) race; calls in stream order do not, and
+ * nothing in the array needs to start at zero (every partial result is written before it is read).  The device
+ * current at sdlm_create is the one whose copy is used.  SDLM_EHIP if the array's address could not be obtained.
+ */
+int sdlm_decode_step_static(sdlm_ctx *ctx, int32_t *ids, int32_t *count, float *conf, float *logits);
+
+/*
  * Replay the decode step as a HIP graph.  The launch sequence of sdlm_decode_step is fixed once the batch is known
  * (row counts, lengths and page tables live in device memory), so with enable != 0 the first sdlm_decode_step after
  * a prefill, or after the output pointers change, captures its launches on the context's stream and later calls

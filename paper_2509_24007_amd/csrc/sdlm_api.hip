@@ -5,6 +5,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -13,7 +14,39 @@
 
 using namespace sdlm;
 
+// Partial-result scratch of sdlm_decode_step_static: split-k slabs, split-KV partial results and the LM head's
+// per-vocabulary-block partials (fp32 mode: the logits when the caller does not ask for them).  One copy per GPU,
+// held until the process ends; every context on a GPU shares it.  In host code this name is only a handle for
+// hipGetSymbolAddress: the device address is looked up once per device and kept in g_static_scratch.
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)32 << 20;
+constexpr size_t STATIC_SLAB_BYTES = (size_t)16 << 20, STATIC_ATTN_BYTES = (size_t)12 << 20;
+constexpr size_t STATIC_LM_BYTES = STATIC_SCRATCH_BYTES - STATIC_SLAB_BYTES - STATIC_ATTN_BYTES;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::mutex g_static_mu;
+void *g_static_scratch[MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device (looked up on first use, with that device current).
+hipError_t static_scratch_of_current_device(void **out)
+{
+    *out = nullptr;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_scratch[dev]) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        g_static_scratch[dev] = p;
+    }
+    *out = g_static_scratch[dev];
+    return hipSuccess;
+}
 
 struct LayerW {
     void *attn_norm, *wqkv, *bqkv, *wo, *ffn_norm, *w_gate, *w_up, *w_down;   // w_gate: fused gate/up when packed
@@ -156,6 +189,10 @@ struct sdlm_ctx {
     bool prefilled = false, stepped = false;
     bool committed = false;              // a commit has happened since the prefill: every sequence has >= 1 pending row
     std::vector<int32_t> n_ub;           // host upper bound of n_b
+    std::vector<int32_t> n_host;         // landing buffer of refresh_lengths (sized once, so that a step allocates nothing)
+    char *static_scratch = nullptr;      // this GPU's copy of the library-owned scratch array (sdlm_decode_step_static)
+    std::string static_err;              // why static_scratch is missing
+    bool no_events = false;              // a call that must not create HIP events is running
     std::vector<Tap> taps;
     // graph replay of the decode step (opt-in): the launch sequence of a step is fixed once the batch is, all sizes
     // that vary from step to step live in device memory
@@ -196,7 +233,7 @@ struct Phase {
     size_t idx = (size_t)-1;
     Phase(sdlm_ctx *c_, int ph) : c(c_)
     {
-        if (!((c->prof >> ph) & 1u)) return;
+        if (!((c->prof >> ph) & 1u) || c->no_events) return;
         if (c->prof_seen[ph]++ % c->prof_every != 0) return;
         if (c->ev_used + 2 > c->ev.size()) {
             hipEvent_t a, b;
@@ -319,7 +356,7 @@ void drop_graph(sdlm_ctx *c)
 
 int refresh_lengths(sdlm_ctx *c, int32_t *flags_out)
 {
-    std::vector<int32_t> n(c->batch);
+    std::vector<int32_t> &n = c->n_host;
     int32_t al[2];
     HIPCHK(c, hipMemcpyAsync(n.data(), c->st.n, sizeof(int32_t) * c->batch, hipMemcpyDeviceToHost, c->stream));
     HIPCHK(c, hipMemcpyAsync(al, c->st.alloc, sizeof al, hipMemcpyDeviceToHost, c->stream));
@@ -390,6 +427,14 @@ int sdlm_create(const sdlm_model_cfg *m, const sdlm_run_cfg *r, void *workspace,
     c->conf_rows = (float *)(ws + L.conf_rows); c->ids_rows = (int32_t *)(ws + L.ids_rows);
     c->attn_part = ws + L.attn_part; c->slabs = (float *)(ws + L.slabs); c->lm_part = ws + L.lm_part;
     c->n_ub.assign(B, 0);
+    c->n_host.assign(B, 0);
+    {
+        void *p = nullptr;
+        hipError_t e = static_scratch_of_current_device(&p);
+        if (e == hipSuccess) c->static_scratch = (char *)p;
+        else c->static_err = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e);
+        (void)hipGetLastError();   // the step's other entry points do not depend on it
+    }
     c->info = L.mfma ? "mfma-bf16" : (m->dtype == 0 ? "generic-fp32" : "generic-bf16");
     // rotary table: (cos, sin)(pos * theta^(-2i/d)), evaluated in double on the host
     const int half = m->head_dim / 2, max_pos = r->max_seq_len + 2 * D;
@@ -561,7 +606,7 @@ int sdlm_prefill(sdlm_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
     return SDLM_OK;
 }
 
-int sdlm_decode_step(sdlm_ctx *c, int32_t *ids, int32_t *count, float *conf, float *logits)
+static int decode_step_impl(sdlm_ctx *c, int32_t *ids, int32_t *count, float *conf, float *logits, bool eager_only)
 {
     if (!c) return SDLM_EINVAL;
     if (!c->prefilled) return fail(c, SDLM_ESTATE, "decode_step before prefill");
@@ -588,7 +633,7 @@ int sdlm_decode_step(sdlm_ctx *c, int32_t *ids, int32_t *count, float *conf, flo
         run_lm_head(c, B * D, logits);
         { Phase p(c, SDLM_PH_ACCEPT); launch_accept(s, c->st, c->ids_rows, c->conf_rows, B, D, c->r.tau, c->r.accept_rule, ids, count, conf); }
     };
-    if (c->graph_on && c->prof == 0 && c->taps.empty()) {
+    if (c->graph_on && c->prof == 0 && c->taps.empty() && !eager_only) {
         void *key[4] = {ids, count, conf, logits};
         if (!c->graph_exec || memcmp(key, c->graph_key, sizeof key) != 0) {
             drop_graph(c);
@@ -609,6 +654,39 @@ int sdlm_decode_step(sdlm_ctx *c, int32_t *ids, int32_t *count, float *conf, flo
     HIPCHK(c, hipGetLastError());
     c->stepped = true;
     return SDLM_OK;
+}
+
+int sdlm_decode_step(sdlm_ctx *c, int32_t *ids, int32_t *count, float *conf, float *logits)
+{
+    return decode_step_impl(c, ids, count, conf, logits, false);
+}
+
+int sdlm_decode_step_static(sdlm_ctx *c, int32_t *ids, int32_t *count, float *conf, float *logits)
+{
+    if (!c) return SDLM_EINVAL;
+    if (!c->static_scratch) return fail(c, SDLM_EHIP, "the library's static scratch array is unavailable: %s", c->static_err.c_str());
+    if (!c->prefilled) return fail(c, SDLM_ESTATE, "decode_step before prefill");
+    // what must fit: the LM head's partials of batch x D rows (fp32 mode: their logits, unless the caller takes them)
+    const size_t lm_rows = (size_t)c->batch * c->r.block_D;
+    const size_t lm_need = c->L.mfma ? mfma_lm_scratch_bytes(c->m.vocab, (int)lm_rows) : (logits ? 0 : lm_rows * c->m.vocab * sizeof(float));
+    if (lm_need > STATIC_LM_BYTES)
+        return fail(c, SDLM_ECAPACITY, "sdlm_decode_step_static: batch %d x D %d x vocabulary %d needs %zu bytes of LM-head scratch, the static array has %zu",
+                    c->batch, c->r.block_D, c->m.vocab, lm_need, STATIC_LM_BYTES);
+    // Point the step's partial-result scratch at the static array for the duration of the launches (the kernels take
+    // the addresses as arguments); split counts and KV chunking adapt to the room they are given.
+    struct Saved { float *slabs; size_t slab_floats; void *attn_part; size_t attn_bytes; void *lm_part; float *logits; } sv =
+        {c->slabs, c->L.slab_floats, c->attn_part, c->L.attn_bytes, c->lm_part, c->logits};
+    char *base = c->static_scratch;
+    c->slabs = (float *)base; c->L.slab_floats = c->L.mfma ? STATIC_SLAB_BYTES / sizeof(float) : sv.slab_floats;
+    c->attn_part = base + STATIC_SLAB_BYTES; c->L.attn_bytes = STATIC_ATTN_BYTES;
+    c->lm_part = base + STATIC_SLAB_BYTES + STATIC_ATTN_BYTES;
+    c->logits = (float *)c->lm_part;
+    c->no_events = true;
+    const int rc = decode_step_impl(c, ids, count, conf, logits, true);
+    c->no_events = false;
+    c->slabs = sv.slabs; c->L.slab_floats = sv.slab_floats; c->attn_part = sv.attn_part; c->L.attn_bytes = sv.attn_bytes;
+    c->lm_part = sv.lm_part; c->logits = sv.logits;
+    return rc;
 }
 
 int sdlm_graph(sdlm_ctx *c, int32_t enable)

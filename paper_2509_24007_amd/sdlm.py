@@ -19,7 +19,7 @@ PHASES = ("rows", "norm", "qkv", "rope", "attn", "oproj", "gateup", "down", "lmh
 OK, EINVAL, ECAPACITY, ESTATE, EHIP = 0, -1, -2, -3, -4
 
 EXPORTS = ("sdlm_workspace_bytes", "sdlm_create", "sdlm_init_weights", "sdlm_prefill", "sdlm_decode_step",
-           "sdlm_graph", "sdlm_verify_step", "sdlm_kv_commit", "sdlm_get_lengths", "sdlm_debug_tap", "sdlm_debug_rows", "sdlm_debug_read_kv",
+           "sdlm_decode_step_static", "sdlm_graph", "sdlm_verify_step", "sdlm_kv_commit", "sdlm_get_lengths", "sdlm_debug_tap", "sdlm_debug_rows", "sdlm_debug_read_kv",
            "sdlm_debug_gemm_plan", "sdlm_max_rows", "sdlm_profile", "sdlm_profile_every", "sdlm_profile_read", "sdlm_kernel_info", "sdlm_last_error",
            "sdlm_destroy")
 
@@ -70,6 +70,8 @@ def load():
     L.sdlm_prefill.argtypes = [vp, i32, vp, vp]
     L.sdlm_decode_step.restype = C.c_int
     L.sdlm_decode_step.argtypes = [vp, vp, vp, vp, vp]
+    L.sdlm_decode_step_static.restype = C.c_int
+    L.sdlm_decode_step_static.argtypes = [vp, vp, vp, vp, vp]
     L.sdlm_debug_gemm_plan.restype = C.c_int
     L.sdlm_debug_gemm_plan.argtypes = [C.c_int32] * 5 + [vp, vp, vp]
     L.sdlm_graph.restype = C.c_int
@@ -244,14 +246,16 @@ class Context:
         self.batch = len(prompts)
 
     def decode_step(self, ids: torch.Tensor, count: torch.Tensor, conf: Optional[torch.Tensor] = None,
-                    logits: Optional[torch.Tensor] = None) -> None:
+                    logits: Optional[torch.Tensor] = None, static_scratch: bool = False) -> None:
+        """static_scratch=True calls sdlm_decode_step_static (partial results in the library's static array)."""
         B, D = self.batch, self.D
         assert ids.dtype == torch.int32 and ids.numel() >= B * D and ids.is_cuda and ids.is_contiguous()
         assert count.dtype == torch.int32 and count.numel() >= B and count.is_cuda
         assert conf is None or (conf.dtype == torch.float32 and conf.numel() >= B * D and conf.is_cuda and conf.is_contiguous())
         assert logits is None or (logits.dtype == torch.float32 and logits.numel() >= B * D * self.m.vocab and
                                   logits.is_cuda and logits.is_contiguous())
-        self._check(self.L.sdlm_decode_step(self.h, _dp(ids), _dp(count), _dp(conf), _dp(logits)))
+        fn = self.L.sdlm_decode_step_static if static_scratch else self.L.sdlm_decode_step
+        self._check(fn(self.h, _dp(ids), _dp(count), _dp(conf), _dp(logits)))
 
     def graph(self, enable: bool = True) -> None:
         """Replay decode_step as a HIP graph (the context must have been created on a non-default stream)."""
