@@ -48,7 +48,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true", help="also time the other thresholds of the workload's tau sweep")
     ap.add_argument("--phases", default="gateup",
-                    help="phases bracketed by HIP events inside the timed region: one phase name (default: the dominant kernel), "
+                    help="phases bracketed by HIP events inside the timed region: phase names separated by commas (default: the dominant kernel), "
                          "main (all six big kernels, ~6%% slower steps) or none; the per-kernel table of the other phases comes "
                          "from up to 32 extra untimed steps")
     ap.add_argument("--profile-every", type=int, default=9,
@@ -232,7 +232,7 @@ def main():
     t0 = time.perf_counter()
     host_g, host_layers = build_model(ctx, m, wl.seed, keep_host_layers=m.n_layers if want_cpu else None)
     t_build = time.perf_counter() - t0
-    prof = True if a.profile_all else {"main": MAIN_PHASES, "none": None}.get(a.phases, (a.phases,))
+    prof = True if a.profile_all else {"main": MAIN_PHASES, "none": None}.get(a.phases, tuple(a.phases.split(",")))
     if a.verify is not None:
         prof = None
     esz = 4 if m.dtype == "fp32" else 2

@@ -50,6 +50,7 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
     // two tile pairs depend on the sequence and the chunk alone, so each is requested one step early: three memory
     // round trips before the first K/V request instead of five.
     const int n_groups = a.rm.counts[1];
+    const int cp = max(a.rm.counts[3], a.chunk_pages);   // tiles per KV chunk: chosen on the device from the actual lengths, never below the host's floor
     const int row0 = a.rm.grp_row0[g], nrows = a.rm.grp_n[g], b = a.rm.grp_seq[g];
     if (g >= n_groups) return;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -58,7 +59,7 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
     const int32_t *ptab = a.st.page_table + (size_t)b * a.kg.pages_per_seq;
     int pg_first[4];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) pg_first[u] = ptab[min(chunk * a.chunk_pages + u, a.kg.pages_per_seq - 1)];
+    for (int u = 0; u < 4; ++u) pg_first[u] = ptab[min(chunk * cp + u, a.kg.pages_per_seq - 1)];
 
     int lim_l = lane < nrows ? a.rm.lim[row0 + lane] : 0;
     int blk_l = lane < nrows ? (a.rm.smask[row0 + lane] != 0 ? 1 : 0) : 0;
@@ -70,9 +71,9 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
     }
     const int max_lim = lim_l, min_lim = min_l, any_blk = blk_l;
     const int n_pages = (max_lim + PAGE - 1) / PAGE;
-    const int n_chunks = max(1, (n_pages + a.chunk_pages - 1) / a.chunk_pages);
+    const int n_chunks = max(1, (n_pages + cp - 1) / cp);
     if (chunk >= n_chunks) return;
-    const int c0 = chunk * a.chunk_pages, c1 = min(n_pages, c0 + a.chunk_pages);
+    const int c0 = chunk * cp, c1 = min(n_pages, c0 + cp);
     const int n_cache = c1 - c0;
     const int nv = n_cache + ((chunk == 0 && any_blk) ? 1 : 0);   // virtual tiles of this chunk; the last may be staging
     const int n_pairs = (nv + 1) / 2;
@@ -244,6 +245,7 @@ __global__ __launch_bounds__(256) void attn_combine_k(AttnArgs a)
     const int g = blockIdx.x, hk = blockIdx.y, nq = blockIdx.z, tid = threadIdx.x, lane = tid & 63;
     const size_t item0 = ((size_t)g * a.kg.n_kv_heads + hk) * a.max_chunks;
     const int n_groups = a.rm.counts[1];
+    const int cp = max(a.rm.counts[3], a.chunk_pages);
     const int row0 = a.rm.grp_row0[g], nrows = a.rm.grp_n[g];   // in bounds for every group of the grid
     const int mq = tid & 15, mc = tid >> 4;
     float2 ml0 = make_float2(0.f, 0.f);
@@ -262,7 +264,7 @@ __global__ __launch_bounds__(256) void attn_combine_k(AttnArgs a)
     int lim = lane < nrows ? a.rm.lim[row0 + lane] : 0;   // a group has at most QMAX rows: every wavefront finds the maximum itself
     for (int o = 32; o > 0; o >>= 1) lim = max(lim, __shfl_xor(lim, o));
     const int n_pages = (lim + PAGE - 1) / PAGE;
-    const int n_chunks = max(1, (n_pages + a.chunk_pages - 1) / a.chunk_pages);
+    const int n_chunks = max(1, (n_pages + cp - 1) / cp);
     if (n_chunks == 1) return;   // the attention kernel wrote the final result itself
     __shared__ float sf[16][65], sl[16][65];   // [query][chunk]: running maximum, then 2^{c(m_c - M)} / L; row sum
     for (int c = mc; c < n_chunks; c += 16) {
@@ -325,6 +327,27 @@ static void chunking(const sdlm_model_cfg *m, int max_seq_len, int groups, int *
     *max_chunks = (pages + cp - 1) / cp;
 }
 
+// The smallest chunk size a launch over `groups` row groups may use (the device may pick a larger one from the actual
+// lengths, see attn_chunk_pages): the policy above, made coarser until the partial results fit the scratch area.
+static void chunk_floor(const sdlm_model_cfg *m, int max_seq_len, int groups, size_t scratch_bytes, int *chunk_pages, int *max_chunks)
+{
+    chunking(m, max_seq_len, groups, chunk_pages, max_chunks);
+    const int pages = (max_seq_len + PAGE - 1) / PAGE;
+    size_t items = (size_t)groups * m->n_kv_heads * *max_chunks;
+    while (*max_chunks > 1 && items * ((size_t)QMAX * HD * 4 + QMAX * 8) > scratch_bytes) {
+        *chunk_pages *= 2;
+        *max_chunks = (pages + *chunk_pages - 1) / *chunk_pages;
+        items = (size_t)groups * m->n_kv_heads * *max_chunks;
+    }
+}
+
+int mfma_attn_chunk_floor(const sdlm_model_cfg *m, int max_seq_len, int groups, size_t scratch_bytes)
+{
+    int cp, mc;
+    chunk_floor(m, max_seq_len, groups, scratch_bytes, &cp, &mc);
+    return cp;
+}
+
 size_t mfma_attn_scratch_bytes(const sdlm_model_cfg *m, const sdlm_run_cfg *r, int max_rows)
 {
     if (!mfma_supported(m)) return 256;
@@ -352,14 +375,8 @@ bool launch_attn_mfma(hipStream_t s, const sdlm_model_cfg *m, int max_seq_len, c
     AttnArgs a;
     a.q = (const bf16_t *)q; a.out = (bf16_t *)out; a.pool = (const bf16_t *)pool_layer;
     a.kg = kg; a.rm = rm; a.st = st; a.Hq = m->n_q_heads; a.G = m->n_q_heads / m->n_kv_heads; a.D = D;
-    chunking(m, max_seq_len, max_groups, &a.chunk_pages, &a.max_chunks);
-    const int pages = (max_seq_len + PAGE - 1) / PAGE;
-    size_t items = (size_t)max_groups * kg.n_kv_heads * a.max_chunks;
-    while (a.max_chunks > 1 && items * ((size_t)QMAX * HD * 4 + QMAX * 8) > scratch_bytes) {   // coarser chunks until the partials fit
-        a.chunk_pages *= 2;
-        a.max_chunks = (pages + a.chunk_pages - 1) / a.chunk_pages;
-        items = (size_t)max_groups * kg.n_kv_heads * a.max_chunks;
-    }
+    chunk_floor(m, max_seq_len, max_groups, scratch_bytes, &a.chunk_pages, &a.max_chunks);
+    const size_t items = (size_t)max_groups * kg.n_kv_heads * a.max_chunks;
     a.part_o = (float *)scratch;
     a.part_ml = (float2 *)((char *)scratch + items * QMAX * HD * 4);
     a.c = 1.4426950408889634f / sqrtf((float)HD);

@@ -57,6 +57,17 @@ template <> __device__ inline bf16_t from_f<bf16_t>(float v) { return f_to_bf16(
 __host__ __device__ inline int k_off(int slot, int i) { return (i >> 3) * (PAGE * 8) + slot * 8 + (i & 7); }
 __host__ __device__ inline int v_off(int slot, int i) { return (((i >> 4) << 2) + (slot >> 2)) * 64 + ((i & 15) << 2) + (slot & 3); }
 
+// Tiles per KV chunk for an attention launch whose (row group, kv head) items cover `item_pages` 16-key tiles in all:
+// large enough that the launch has about 2.25 work items per compute unit (measured on the 7B and 32B shapes: all work
+// items resident at once, two to three per unit, is the fastest split; finer chunks only add partial results to merge),
+// a multiple of 8, and never below `floor_pages` (the host's bound: partial-result scratch, 64 chunks per item).
+__host__ __device__ inline int attn_chunk_pages(long item_pages, int floor_pages)
+{
+    long cp = (item_pages + 575) / 576;
+    cp = (cp + 7) / 8 * 8;
+    return cp > floor_pages ? (int)cp : floor_pages;
+}
+
 // Packed description of the rows of one forward pass (device arrays).
 struct RowMeta {
     int32_t *tok, *pos, *seq, *kind, *lim;  // [max_rows]; kind: -1 = K/V go to the cache slot of pos, else the slot in the
@@ -65,7 +76,7 @@ struct RowMeta {
     int32_t *grp_row0, *grp_n, *grp_seq;    // [max_groups]: runs of <= GROUP_ROWS rows of one sequence that share a staging tile
     int32_t *grp_stg;                       // [max_groups]: that staging tile (-1: none)
     int32_t *blk_row;                       // [max_batch*D]: packed row index of the rows that go through the LM head
-    int32_t *counts;                        // [4]: rows R, groups, LM-head rows, unused
+    int32_t *counts;                        // [4]: rows R, groups, LM-head rows, tiles per KV chunk of the attention launch
 };
 
 // Per-sequence state (device arrays).
@@ -102,12 +113,12 @@ struct GemmArgs {
 };
 
 void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows,
-                            int staging_base, int causal);
+                            int staging_base, int causal, int n_kv_heads, int chunk_floor);
 // Rows one sequence contributes to a verification pass, and whether they share one staging tile (the layout for
 // block sizes whose D-2 causal rows and (D-1) D block rows fit the 16 slots of a tile) or take one tile per input.
 int verify_rows_per_seq(int D, bool *shared_tile);
 void launch_assemble_verify(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows,
-                            int staging_base, int causal);
+                            int staging_base, int causal, int n_kv_heads, int chunk_floor);
 void launch_verify_accept(hipStream_t s, const SeqState &st, const int32_t *ids_rows, int B, int D, int rule,
                           int32_t *ids_out, int32_t *count_out);
 void launch_embed(hipStream_t s, int dtype, float *x, const void *E, const RowMeta &rm, int max_rows, int h, int V);

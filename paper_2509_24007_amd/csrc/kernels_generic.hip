@@ -10,19 +10,21 @@ namespace sdlm {
 // Rows of a decode step, per sequence: the pending tokens (positions c..n-1, causal), then the block
 // [x_last, [m] x (D-1)] at positions n-1 .. n+D-2 (block definition, Sec. 3.2).  A block row may see the cache
 // below position s = n-1 only; the causal copy of x_last at s is for later steps.
-__global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mask_id, int gr, int stg0, int causal)
+__global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mask_id, int gr, int stg0, int causal, int Hkv, int cp_floor)
 {
     __shared__ int row0[1025], grp0[1025];
     if (threadIdx.x == 0) {
         int r = 0, g = 0;
+        long tiles = 0;   // 16-key tiles the attention's work items stream, per kv head
         for (int b = 0; b < B; ++b) {
             row0[b] = r; grp0[b] = g;
-            int rows = st.n[b] - st.c[b] + D;
+            int rows = st.n[b] - st.c[b] + D, ng = (rows + gr - 1) / gr;
             r += rows;
-            g += (rows + gr - 1) / gr;
+            g += ng;
+            tiles += (long)ng * ((st.n[b] + PAGE - 1) / PAGE);
         }
         row0[B] = r; grp0[B] = g;
-        rm.counts[0] = r; rm.counts[1] = g; rm.counts[2] = B * D; rm.counts[3] = 0;
+        rm.counts[0] = r; rm.counts[1] = g; rm.counts[2] = B * D; rm.counts[3] = attn_chunk_pages(tiles * Hkv, cp_floor);
     }
     __syncthreads();
     for (int b = threadIdx.x; b < B; b += blockDim.x) {
@@ -49,9 +51,9 @@ __global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mas
 }
 
 void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows, int staging_base,
-                            int causal)
+                            int causal, int n_kv_heads, int chunk_floor)
 {
-    hipLaunchKernelGGL(assemble_decode_k, dim3(1), dim3(256), 0, s, st, rm, B, D, mask_id, group_rows, staging_base, causal);
+    hipLaunchKernelGGL(assemble_decode_k, dim3(1), dim3(256), 0, s, st, rm, B, D, mask_id, group_rows, staging_base, causal, n_kv_heads, chunk_floor);
 }
 
 // Rows of the verification pass of a self-speculative step (Sec. 3.4, "Self-Speculative Decoding").  With yhat^1..yhat^D
@@ -65,18 +67,20 @@ void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm
 // sees all j-2+D slots.  Nothing is written to the cache.  Only the first block row of each input goes through the
 // LM head: its arg-max is ytilde^j.  When all rows of a sequence fit one tile (shared != 0) the causal rows are
 // computed once for all inputs; see below.
-__global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mask_id, int gr, int stg0, int causal, int shared)
+__global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mask_id, int gr, int stg0, int causal, int shared, int Hkv, int cp_floor)
 {
     __shared__ int row0[1025], grp0[1025];
     const int rows_seq = shared ? (D - 2) + (D - 1) * D : (D - 1) * D + (D - 2) * (D - 1) / 2;
     if (threadIdx.x == 0) {
         int g = 0;
+        long tiles = 0;
         for (int b = 0; b < B; ++b) {
             row0[b] = b * rows_seq; grp0[b] = g;
             if (shared) g += (rows_seq + gr - 1) / gr;
             else for (int j = 2; j <= D; ++j) g += (j - 2 + D + gr - 1) / gr;
+            tiles += (long)(g - grp0[b]) * ((st.n[b] + PAGE - 1) / PAGE);
         }
-        rm.counts[0] = B * rows_seq; rm.counts[1] = g; rm.counts[2] = B * (D - 1); rm.counts[3] = 0;
+        rm.counts[0] = B * rows_seq; rm.counts[1] = g; rm.counts[2] = B * (D - 1); rm.counts[3] = attn_chunk_pages(tiles * Hkv, cp_floor);
     }
     __syncthreads();
     for (int b = threadIdx.x; b < B; b += blockDim.x) {
@@ -139,11 +143,12 @@ int verify_rows_per_seq(int D, bool *shared_tile)
 }
 
 void launch_assemble_verify(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows,
-                            int staging_base, int causal)
+                            int staging_base, int causal, int n_kv_heads, int chunk_floor)
 {
     bool shared;
     verify_rows_per_seq(D, &shared);
-    hipLaunchKernelGGL(assemble_verify_k, dim3(1), dim3(256), 0, s, st, rm, B, D, mask_id, group_rows, staging_base, causal, shared ? 1 : 0);
+    hipLaunchKernelGGL(assemble_verify_k, dim3(1), dim3(256), 0, s, st, rm, B, D, mask_id, group_rows, staging_base, causal, shared ? 1 : 0, n_kv_heads,
+                       chunk_floor);
 }
 
 // gamma_verify (Eq. 10) from the step's tokens yhat and the verification predictions (ids_rows: ytilde^2..ytilde^D per

@@ -14,6 +14,8 @@ size_t mfma_packed_elems(bool packed, size_t N, size_t K);
 size_t mfma_attn_scratch_bytes(const sdlm_model_cfg *m, const sdlm_run_cfg *r, int max_rows);
 // Bytes of scratch for the LM head's per-vocabulary-block partials.
 size_t mfma_lm_scratch_bytes(int V, int max_rows);
+// Smallest KV chunk (in 16-key tiles) the attention launch over `groups` row groups may use with this much scratch.
+int mfma_attn_chunk_floor(const sdlm_model_cfg *m, int max_seq_len, int groups, size_t scratch_bytes);
 // Rows of one sequence that form one attention work item (rows x query heads per kv head <= 64).
 int mfma_group_rows(const sdlm_model_cfg *m);
 

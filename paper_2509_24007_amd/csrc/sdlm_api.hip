@@ -574,7 +574,7 @@ int sdlm_prefill(sdlm_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
             g0.push_back(r0); gn.push_back(r1 - r0); gs.push_back(seq[r0]);
             r0 = r1;
         }
-        int32_t counts[4] = {R, (int32_t)g0.size(), 0, 0};
+        int32_t counts[4] = {R, (int32_t)g0.size(), 0, c->L.mfma ? mfma_attn_chunk_floor(&c->m, c->r.max_seq_len, (int)g0.size(), c->L.attn_bytes) : 0};
         const std::vector<int32_t> none((size_t)R, -1), zero((size_t)R, 0);   // causal rows: no staging tile
         HIPCHK(c, hipMemcpyAsync(c->rm.stg, none.data(), R * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.smask, zero.data(), R * 4, hipMemcpyHostToDevice, s));
@@ -627,9 +627,10 @@ static int decode_step_impl(sdlm_ctx *c, int32_t *ids, int32_t *count, float *co
     }
     hipStream_t s = c->stream;
     auto launch_all = [&]() {
-        const int rows = B * 2 * D;
-        { Phase p(c, SDLM_PH_ROWS); launch_assemble_decode(s, c->st, c->rm, B, D, c->m.mask_token_id, c->L.group_rows, c->kg.staging_base, c->m.block_causal); }
-        run_layers(c, rows, B * ((2 * D + c->L.group_rows - 1) / c->L.group_rows), B * (D + (c->committed ? 1 : 0)));   // after a commit every sequence has >= 1 pending row
+        const int rows = B * 2 * D, groups = B * ((2 * D + c->L.group_rows - 1) / c->L.group_rows);
+        const int cp_floor = c->L.mfma ? mfma_attn_chunk_floor(&c->m, c->r.max_seq_len, groups, c->L.attn_bytes) : 0;
+        { Phase p(c, SDLM_PH_ROWS); launch_assemble_decode(s, c->st, c->rm, B, D, c->m.mask_token_id, c->L.group_rows, c->kg.staging_base, c->m.block_causal, c->m.n_kv_heads, cp_floor); }
+        run_layers(c, rows, groups, B * (D + (c->committed ? 1 : 0)));   // after a commit every sequence has >= 1 pending row
         run_lm_head(c, B * D, logits);
         { Phase p(c, SDLM_PH_ACCEPT); launch_accept(s, c->st, c->ids_rows, c->conf_rows, B, D, c->r.tau, c->r.accept_rule, ids, count, conf); }
     };
@@ -717,7 +718,8 @@ int sdlm_verify_step(sdlm_ctx *c, int32_t rule, int32_t *ids_tilde, int32_t *cou
         int groups = 0;
         if (shared) groups = (rows_seq + gr - 1) / gr;
         else for (int j = 2; j <= D; ++j) groups += (j - 2 + D + gr - 1) / gr;
-        { Phase p(c, SDLM_PH_ROWS); launch_assemble_verify(s, c->st, c->rm, B, D, c->m.mask_token_id, gr, c->kg.staging_base, c->m.block_causal); }
+        const int cp_floor = c->L.mfma ? mfma_attn_chunk_floor(&c->m, c->r.max_seq_len, B * groups, c->L.attn_bytes) : 0;
+        { Phase p(c, SDLM_PH_ROWS); launch_assemble_verify(s, c->st, c->rm, B, D, c->m.mask_token_id, gr, c->kg.staging_base, c->m.block_causal, c->m.n_kv_heads, cp_floor); }
         run_layers(c, rows, B * groups, rows);
         run_lm_head(c, B * (D - 1), logits);
     }
