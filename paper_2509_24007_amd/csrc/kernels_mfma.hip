@@ -67,6 +67,7 @@ struct MfmaArgs {
     const int32_t *pR;
     int max_rows, N, K, n_tiles, n_blocks, m_blocks, splits, stages_per_split, n_out;   // n_out: row length of the destination
     int m_sure;         // row blocks below this index certainly hold rows; they come first in the grid
+    int rows_sure;      // rows below this index certainly exist (host-known lower bound of the device row count)
     size_t slab;        // elements between split-k slabs
     float scale;
 };
@@ -85,7 +86,6 @@ __global__ __launch_bounds__(256, (MT == 4 ? 2 : 1)) void gemm_mfma_k(MfmaArgs a
     __shared__ __attribute__((aligned(16))) bf16_t Xs[2][MT * 32][XS_STRIDE];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform: keeps the weight stream's base in SGPRs
-    const int R = min(*a.pR, a.max_rows);
     // workgroup id -> tile.  The grid has two parts: the row blocks that certainly hold rows (mblk < m_sure), then the
     // others, which usually exit at once; mixing them would leave the compute units that draw an empty block idle.
     // Within a part, ids that land on one XCD (id % 8) get consecutive tiles, the row blocks of one weight band first.
@@ -103,6 +103,9 @@ __global__ __launch_bounds__(256, (MT == 4 ? 2 : 1)) void gemm_mfma_k(MfmaArgs a
     }
     const int split = rest % a.splits, nblk = rest / a.splits;
     const int m0 = mblk * MT * 32;
+    // A row block that lies entirely below the host-known row bound does not wait for the device-side row count: its
+    // first operand requests go out at once (the count is one more memory round trip at the head of the kernel).
+    const int R = m0 + MT * 32 <= a.rows_sure ? a.rows_sure : min(*a.pR, a.max_rows);
     if (m0 >= R) return;
     const int KS = a.K >> 4, S = a.K >> 6;
     const int s_begin = split * a.stages_per_split, s_end = min(S, s_begin + a.stages_per_split);
@@ -587,6 +590,7 @@ static void launch_cfg(hipStream_t s, const TileChoice &c, MfmaArgs &a, int min_
     int S = a.K / 64;
     a.stages_per_split = (S + c.splits - 1) / c.splits;
     a.m_sure = sure_blocks(a.max_rows, min_rows, c.MT);
+    a.rows_sure = min_rows < 0 ? 0 : (min_rows > a.max_rows ? a.max_rows : min_rows);
     const int first = a.n_blocks * a.splits * a.m_sure, rest = a.n_blocks * a.splits * (a.m_blocks - a.m_sure);
     dim3 grid((first + 7) / 8 * 8 + (rest + 7) / 8 * 8), block(256);
 #define SDLM_GO(MT_, NT_) hipLaunchKernelGGL((gemm_mfma_k<MT_, NT_, EPI>), grid, block, 0, s, a)
