@@ -359,7 +359,7 @@ def main():
     if a.verify is not None:    # the byte accounting above describes the block step alone
         for k in ("step_algorithmic_GB", "step_hbm_GBs", "step_hbm_frac", "step_hbm_frac_of_copy_ceiling", "roofline"):
             out[k] = None
-        out["verify_rows_per_step"] = B * ((D - 2) + (D - 1) * D if (D - 2) + (D - 1) * D <= 16 else (D - 1) * D + (D - 2) * (D - 1) // 2)
+        out["verify_rows_per_step"] = B * ((D - 2) + (D - 1) * D)
     if len(results) > 1:
         out["tau_sweep"] = [dict(tau=x["tau"], value=x["accepted"] / x["dt"], ms_per_step=1e3 * x["dt"] / a.steps,
                                  gamma_hist=x["hist"]) for x in results]

@@ -181,7 +181,8 @@ int sdlm_graph(sdlm_ctx *ctx, int32_t enable);
  *              without overrides publishes yhat^1..yhat^{gamma_verify}.
  *   logits     [dev, batch x (D-1) x vocab] fp32 logits from which ytilde^2..ytilde^D were taken, or NULL.
  * Asynchronous on the context's stream.  Errors: SDLM_ESTATE without a preceding step, SDLM_EINVAL for an unknown
- * rule or when 2D-2 exceeds the 16 slots of a staging tile (block_D > 9).
+ * rule.  Every block size 1..16 is served; a sequence contributes (D-2) + (D-1) D rows to the pass (the causal rows
+ * of the speculative tokens are shared by all inputs).
  */
 int sdlm_verify_step(sdlm_ctx *ctx, int32_t rule, int32_t *ids_tilde, int32_t *count, float *logits);
 

@@ -10,7 +10,7 @@
 // operands from LDS with conflict-free 16-byte / 8-byte reads.  Each of the four wavefronts owns 16 of the (at
 // most 64) query vectors, so its state is small (32 accumulator registers) and four workgroups fit on a CU.
 // The mask of the method lives in registers: every row sees cache keys [0, lim) and the slots of the group's
-// staging tile that its slot mask names.  A pending row at position p has lim = p + 1 and no staging slots; a block row has lim = s
+// staging tiles that its slot masks name (its own tile, and for a verification block the tile of the shared causal rows).  A pending row at position p has lim = p + 1 and no staging slots; a block row has lim = s
 // and the D keys of its own block in the staging tile.
 // Chunks of one (group, head) are merged by a second small kernel when there is more than one.
 #include "mfma.hpp"
@@ -62,7 +62,7 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
     for (int u = 0; u < 4; ++u) pg_first[u] = ptab[min(chunk * cp + u, a.kg.pages_per_seq - 1)];
 
     int lim_l = lane < nrows ? a.rm.lim[row0 + lane] : 0;
-    int blk_l = lane < nrows ? (a.rm.smask[row0 + lane] != 0 ? 1 : 0) : 0;
+    int blk_l = lane < nrows ? a.rm.smask[row0 + lane] : 0;   // OR over the group's rows: which staging tiles are seen at all
     int min_l = lane < nrows ? lim_l : 0x7fffffff;
     for (int o = 32; o > 0; o >>= 1) {
         lim_l = max(lim_l, __shfl_xor(lim_l, o));
@@ -75,7 +75,10 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
     if (chunk >= n_chunks) return;
     const int c0 = chunk * cp, c1 = min(n_pages, c0 + cp);
     const int n_cache = c1 - c0;
-    const int nv = n_cache + ((chunk == 0 && any_blk) ? 1 : 0);   // virtual tiles of this chunk; the last may be staging
+    // Staging tiles follow the cache tiles of chunk 0: first the group's second tile (if a row sees it: upper half of
+    // the slot masks), then its own tile (lower half).
+    const bool has1 = (any_blk & 0xffff) != 0, has2 = ((uint32_t)any_blk >> 16) != 0;
+    const int nv = n_cache + (chunk == 0 ? (int)has1 + (int)has2 : 0);   // virtual tiles of this chunk; the last ones may be staging
     const int n_pairs = (nv + 1) / 2;
 
     // This wavefront's 16 queries: B operands, lane (n = lane%16, group lg) holds q[32 kk + 8 lg .. +8] of query 16 wave + n
@@ -103,7 +106,8 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
     // through LDS in the cache's own operand order; two LDS buffers, the next two pairs ride in registers meanwhile.
     __shared__ __attribute__((aligned(16))) bf16_t kv[2][2][2 * PAGE * HD];   // [buffer][tile A/B][K block | V block]
     const size_t tile_elems = 2 * PAGE * HD;
-    const int stg_page = max(a.rm.grp_stg[g], 0);
+    const int stg_page = max(a.rm.grp_stg[g], 0), stg2_page = max(a.rm.grp_stg2[g], 0);
+    auto stg_of = [&](int u) { return (has2 && u == n_cache) ? stg2_page : stg_page; };   // staging tile behind virtual tile u >= n_cache
     u32x4 rA[4], rB[4];   // two tile pairs in flight: the next one and the one after it
     auto fetch_pages = [&](int pgA, int pgB, u32x4 (&r)[4]) {
         const bf16_t *tA = a.pool + ((size_t)pgA * a.kg.n_kv_heads + hk) * tile_elems;
@@ -115,14 +119,14 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
     };
     auto fetch = [&](int pp, u32x4 (&r)[4]) {
         const int uA = 2 * pp, uB = 2 * pp + 1;
-        const int pgA = uA >= n_cache ? stg_page : ptab[c0 + uA];
-        const int pgB = uB >= nv ? pgA : (uB >= n_cache ? stg_page : ptab[c0 + uB]);
+        const int pgA = uA >= n_cache ? stg_of(uA) : ptab[c0 + uA];
+        const int pgB = uB >= nv ? pgA : (uB >= n_cache ? stg_of(uB) : ptab[c0 + uB]);
         fetch_pages(pgA, pgB, r);
     };
     auto fetch_first = [&](int pA, int pB, int uA, u32x4 (&r)[4]) {   // pairs 0 and 1: page ids requested at the top
         const int uB = uA + 1;
-        const int pgA = uA >= n_cache ? stg_page : pA;
-        const int pgB = uB >= nv ? pgA : (uB >= n_cache ? stg_page : pB);
+        const int pgA = uA >= n_cache ? stg_of(uA) : pA;
+        const int pgB = uB >= nv ? pgA : (uB >= n_cache ? stg_of(uB) : pB);
         fetch_pages(pgA, pgB, r);
     };
     auto stash = [&](int buf, const u32x4 (&r)[4]) {
@@ -151,10 +155,13 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
             const bool fullB = hasB && !stgB && (c0 + uB + 1) * PAGE <= min_lim;
             if (!(fullA && fullB)) {
                 const int keyA = (c0 + uA) * PAGE + lg * 4, keyB = (c0 + uB) * PAGE + lg * 4;
+                // slot masks of the staging tile behind A / B: the second tile's are the upper half of the row's mask
+                const uint32_t mA = (has2 && uA == n_cache) ? smask_q >> 16 : smask_q & 0xffffu;
+                const uint32_t mB = (has2 && uB == n_cache) ? smask_q >> 16 : smask_q & 0xffffu;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
-                    bool visA = stgA ? ((smask_q >> (lg * 4 + v)) & 1u) != 0 : (keyA + v < lim_q);
-                    bool visB = hasB && (stgB ? ((smask_q >> (lg * 4 + v)) & 1u) != 0 : (keyB + v < lim_q));
+                    bool visA = stgA ? ((mA >> (lg * 4 + v)) & 1u) != 0 : (keyA + v < lim_q);
+                    bool visB = hasB && (stgB ? ((mB >> (lg * 4 + v)) & 1u) != 0 : (keyB + v < lim_q));
                     sA[v] = visA ? sA[v] : -INFINITY;
                     sB[v] = visB ? sB[v] : -INFINITY;
                 }
@@ -355,9 +362,9 @@ size_t mfma_attn_scratch_bytes(const sdlm_model_cfg *m, const sdlm_run_cfg *r, i
     // decode: every sequence has at most ceil(2D / gr) groups; prefill: at most max_rows groups of >= 1 row, but
     // then each group is short: bound both by the launch that needs the most (groups x chunks)
     size_t worst = 0;
-    // ... and the verification pass: D-1 inputs per sequence of at most 2D-2 rows each
+    // ... and the verification pass
     int cand[3] = {r->max_batch * ((2 * r->block_D + gr - 1) / gr), max_rows / gr + r->max_batch,
-                   r->max_batch * (r->block_D - 1) * ((2 * r->block_D - 2 + gr - 1) / gr)};
+                   r->max_batch * verify_groups_per_seq(r->block_D, gr)};
     for (int i = 0; i < 3; ++i) {
         if (cand[i] < 1) continue;
         int cp, mc;

@@ -53,7 +53,8 @@ template <> __device__ inline bf16_t from_f<bf16_t>(float v) { return f_to_bf16(
 //   K block: [d/8][16 slots][8]        element (slot, i) at (i/8)*128 + slot*8 + i%8
 //   V block: [d/16][4][16][4 slots]    element (slot, i) at ((i/16)*4 + slot/4)*64 + (i%16)*4 + slot%4
 // Pool order: [layer][tile][kv head][K block | V block].  Tiles n_pages .. n_pages+max_batch-1 of every layer
-// are the per-sequence staging tiles that hold the D block rows' K/V during a step.
+// are the per-sequence staging tiles that hold the D block rows' K/V during a step; the staging tiles of a
+// verification pass follow them.
 __host__ __device__ inline int k_off(int slot, int i) { return (i >> 3) * (PAGE * 8) + slot * 8 + (i & 7); }
 __host__ __device__ inline int v_off(int slot, int i) { return (((i >> 4) << 2) + (slot >> 2)) * 64 + ((i & 15) << 2) + (slot & 3); }
 
@@ -72,9 +73,12 @@ __host__ __device__ inline int attn_chunk_pages(long item_pages, int floor_pages
 struct RowMeta {
     int32_t *tok, *pos, *seq, *kind, *lim;  // [max_rows]; kind: -1 = K/V go to the cache slot of pos, else the slot in the
                                             // row's staging tile; lim: visible cache keys [0, lim)
-    int32_t *stg, *smask;                   // [max_rows]; staging tile of the row (-1: none) and which of its 16 slots the row sees (bit i: slot i)
-    int32_t *grp_row0, *grp_n, *grp_seq;    // [max_groups]: runs of <= GROUP_ROWS rows of one sequence that share a staging tile
-    int32_t *grp_stg;                       // [max_groups]: that staging tile (-1: none)
+    int32_t *stg, *smask;                   // [max_rows]; staging tile of the row (-1: none): its K/V go to slot `kind` of it; bits 0..15
+                                            // of smask: the slots of that tile the row sees; bits 16..31: the slots it sees of stg2
+    int32_t *stg2;                          // [max_rows]; a second staging tile the row reads (-1: none): the shared causal rows of a
+                                            // verification pass
+    int32_t *grp_row0, *grp_n, *grp_seq;    // [max_groups]: runs of <= GROUP_ROWS rows of one sequence that share their staging tiles
+    int32_t *grp_stg, *grp_stg2;            // [max_groups]: those tiles (-1: none)
     int32_t *blk_row;                       // [max_batch*D]: packed row index of the rows that go through the LM head
     int32_t *counts;                        // [4]: rows R, groups, LM-head rows, tiles per KV chunk of the attention launch
 };
@@ -90,8 +94,8 @@ struct SeqState {
 };
 
 struct KvGeom {
-    int32_t n_kv_heads, head_dim, pages_per_seq, staging_base;  // staging tile of sequence b = staging_base + b; the tiles of
-                                                                 // verification input (b, j) follow at staging_base + B + b (D-1) + j
+    int32_t n_kv_heads, head_dim, pages_per_seq, staging_base;  // staging tile of sequence b = staging_base + b; D tiles per
+                                                                 // sequence for a verification pass follow at staging_base + B + b D
     size_t layer_stride;                                         // elements per layer of the pool
     __host__ __device__ size_t tile(int page, int kvh) const { return ((size_t)page * n_kv_heads + kvh) * (size_t)(2 * PAGE * head_dim); }
 };
@@ -114,9 +118,18 @@ struct GemmArgs {
 
 void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows,
                             int staging_base, int causal, int n_kv_heads, int chunk_floor);
-// Rows one sequence contributes to a verification pass, and whether they share one staging tile (the layout for
-// block sizes whose D-2 causal rows and (D-1) D block rows fit the 16 slots of a tile) or take one tile per input.
+// Rows one sequence contributes to a verification pass, (D-2) causal rows + (D-1) D block rows, and whether they share
+// one staging tile (they fit its 16 slots: D <= 4) or take one tile per input plus one for the causal rows.
 int verify_rows_per_seq(int D, bool *shared_tile);
+// Row groups of those rows for groups of at most `gr` rows (one tile: consecutive runs; else the causal rows and every
+// input's block are grouped on their own).
+__host__ __device__ inline int verify_groups_per_seq(int D, int gr)
+{
+    if (D < 2) return 0;
+    const int rows = (D - 2) + (D - 1) * D;
+    if (rows <= PAGE) return (rows + gr - 1) / gr;
+    return (D - 2 + gr - 1) / gr + (D - 1) * ((D + gr - 1) / gr);
+}
 void launch_assemble_verify(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows,
                             int staging_base, int causal, int n_kv_heads, int chunk_floor);
 void launch_verify_accept(hipStream_t s, const SeqState &st, const int32_t *ids_rows, int B, int D, int rule,

@@ -32,12 +32,13 @@ __global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mas
         for (int i = 0; i < p; ++i, ++r) {
             rm.tok[r] = st.pend_tok[b * D + i];
             rm.pos[r] = c + i; rm.seq[r] = b; rm.kind[r] = -1; rm.lim[r] = c + i + 1;
-            rm.stg[r] = -1; rm.smask[r] = 0;
+            rm.stg[r] = -1; rm.smask[r] = 0; rm.stg2[r] = -1;
         }
         for (int j = 0; j < D; ++j, ++r) {
             rm.tok[r] = j == 0 ? st.last_tok[b] : mask_id;
             rm.pos[r] = n - 1 + j; rm.seq[r] = b; rm.kind[r] = j; rm.lim[r] = n - 1;
             rm.stg[r] = stg0 + b; rm.smask[r] = (1 << (causal ? j + 1 : D)) - 1;   // block keys: all D, or (causal variant) up to the row itself
+            rm.stg2[r] = -1;
             rm.blk_row[b * D + j] = r;
         }
         int rows = p + D, g = grp0[b];
@@ -46,6 +47,7 @@ __global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mas
             rm.grp_n[g] = min(gr, rows - o);
             rm.grp_seq[g] = b;
             rm.grp_stg[g] = stg0 + b;
+            rm.grp_stg2[g] = -1;
         }
     }
 }
@@ -58,29 +60,33 @@ void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm
 
 // Rows of the verification pass of a self-speculative step (Sec. 3.4, "Self-Speculative Decoding").  With yhat^1..yhat^D
 // the tokens of the step just computed and n the number of known tokens, verification input j (j = 2..D; input 1 is
-// the step itself) is the sequence extended by yhat^1..yhat^{j-1}.  In the general layout (shared == 0) it is a
-// self-contained run of rows with a staging tile of its own:
+// the step itself) is the sequence extended by yhat^1..yhat^{j-1}:
 //   j-2 causal rows   yhat^1..yhat^{j-2} at positions n..n+j-3
 //   D block rows      [yhat^{j-1}, [m] x (D-1)] at positions n+j-2 ..
 // All of them see the cache keys [0, n) (written by the step: every known token including x_last has its causal K/V
-// there) and keep their own K/V in the input's staging tile: a causal row in slot i sees slots [0, i]; a block row
-// sees all j-2+D slots.  Nothing is written to the cache.  Only the first block row of each input goes through the
-// LM head: its arg-max is ytilde^j.  When all rows of a sequence fit one tile (shared != 0) the causal rows are
-// computed once for all inputs; see below.
+// there) and keep their own K/V in staging tiles; nothing is written to the cache.  The causal row of yhat^i is the
+// same in every input that has it (same token, same position, same visible keys), so it is computed once per sequence:
+// a sequence contributes its D-2 causal rows, then the D block rows of each input, (D-2) + (D-1) D rows in all.  Only the
+// first block row of each input goes through the LM head: its arg-max is ytilde^j.
+//   shared != 0 (all those rows fit the 16 slots of one tile, D <= 4): one tile per sequence; the causal rows sit in slots
+//     0 .. D-3, input j's block in slots D-2 + (j-2) D ..., and its rows see the causal slots 0 .. j-3 and their own block.
+//     The rows of a sequence then form row groups regardless of the input they belong to.
+//   shared == 0: the causal rows live in a tile of their own (the sequence's last staging tile), every input's block in the
+//     input's tile; a block row reads two staging tiles, its input's (slots 0 .. D-1) and the causal one (slots 0 .. j-3,
+//     upper half of its slot mask).  Row groups do not straddle inputs, so a group reads at most these two tiles.
 __global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mask_id, int gr, int stg0, int causal, int shared, int Hkv, int cp_floor)
 {
     __shared__ int row0[1025], grp0[1025];
-    const int rows_seq = shared ? (D - 2) + (D - 1) * D : (D - 1) * D + (D - 2) * (D - 1) / 2;
+    const int rows_seq = (D - 2) + (D - 1) * D;
+    const int groups_seq = verify_groups_per_seq(D, gr);
     if (threadIdx.x == 0) {
-        int g = 0;
         long tiles = 0;
         for (int b = 0; b < B; ++b) {
-            row0[b] = b * rows_seq; grp0[b] = g;
-            if (shared) g += (rows_seq + gr - 1) / gr;
-            else for (int j = 2; j <= D; ++j) g += (j - 2 + D + gr - 1) / gr;
-            tiles += (long)(g - grp0[b]) * ((st.n[b] + PAGE - 1) / PAGE);
+            row0[b] = b * rows_seq; grp0[b] = b * groups_seq;
+            tiles += (long)groups_seq * ((st.n[b] + PAGE - 1) / PAGE);
         }
-        rm.counts[0] = B * rows_seq; rm.counts[1] = g; rm.counts[2] = B * (D - 1); rm.counts[3] = attn_chunk_pages(tiles * Hkv, cp_floor);
+        rm.counts[0] = B * rows_seq; rm.counts[1] = B * groups_seq; rm.counts[2] = B * (D - 1);
+        rm.counts[3] = attn_chunk_pages(tiles * Hkv, cp_floor);
     }
     __syncthreads();
     for (int b = threadIdx.x; b < B; b += blockDim.x) {
@@ -88,21 +94,16 @@ __global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mas
         const int32_t *yhat = st.last_ids + b * D;
         int r = row0[b], g = grp0[b];
         if (shared) {
-            // One tile for the whole sequence.  The causal rows yhat^1 .. yhat^{D-2} are the same in every input that
-            // has them (same token, same position, same visible keys), so they are computed once, in slots 0 .. D-3;
-            // input j's block follows in slots D-2 + (j-2) D ..., and its rows see the causal slots 0 .. j-3 and their
-            // own block.  The rows of a sequence then form row groups regardless of the input they belong to, and the
-            // attention kernel streams the sequence's cache once per group instead of once per input.
-            const int tile = stg0 + B + b * (D - 1);
+            const int tile = stg0 + B + b * D;
             for (int i = 0; i < D - 2; ++i, ++r) {
                 rm.tok[r] = yhat[i]; rm.pos[r] = n + i; rm.seq[r] = b; rm.kind[r] = i; rm.lim[r] = n;
-                rm.stg[r] = tile; rm.smask[r] = (1 << (i + 1)) - 1;
+                rm.stg[r] = tile; rm.smask[r] = (1 << (i + 1)) - 1; rm.stg2[r] = -1;
             }
             for (int j = 2; j <= D; ++j) {
                 const int base = (D - 2) + (j - 2) * D, common = (1 << (j - 2)) - 1;
                 for (int t = 0; t < D; ++t, ++r) {
                     rm.tok[r] = t == 0 ? yhat[j - 2] : mask_id; rm.pos[r] = n + j - 2 + t; rm.seq[r] = b; rm.kind[r] = base + t;
-                    rm.lim[r] = n; rm.stg[r] = tile; rm.smask[r] = common | (((1 << (causal ? t + 1 : D)) - 1) << base);
+                    rm.lim[r] = n; rm.stg[r] = tile; rm.smask[r] = common | (((1 << (causal ? t + 1 : D)) - 1) << base); rm.stg2[r] = -1;
                     if (t == 0) rm.blk_row[b * (D - 1) + (j - 2)] = r;
                 }
             }
@@ -110,26 +111,36 @@ __global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mas
                 rm.grp_row0[g] = row0[b] + o;
                 rm.grp_n[g] = min(gr, rows_seq - o);
                 rm.grp_seq[g] = b;
-                rm.grp_stg[g] = tile;
+                rm.grp_stg[g] = tile; rm.grp_stg2[g] = -1;
             }
             continue;
         }
+        // tiles of sequence b: stg0 + B + b D + (j - 2) for input j, and stg0 + B + b D + (D - 1) for the causal rows
+        const int ctile = stg0 + B + b * D + (D - 1);
+        for (int i = 0; i < D - 2; ++i, ++r) {
+            rm.tok[r] = yhat[i]; rm.pos[r] = n + i; rm.seq[r] = b; rm.kind[r] = i; rm.lim[r] = n;
+            rm.stg[r] = ctile; rm.smask[r] = (1 << (i + 1)) - 1; rm.stg2[r] = -1;
+        }
+        for (int o = 0; o < D - 2; o += gr, ++g) {
+            rm.grp_row0[g] = row0[b] + o;
+            rm.grp_n[g] = min(gr, D - 2 - o);
+            rm.grp_seq[g] = b;
+            rm.grp_stg[g] = ctile; rm.grp_stg2[g] = -1;
+        }
         for (int j = 2; j <= D; ++j) {
-            const int tile = stg0 + B + b * (D - 1) + (j - 2), ns = j - 2 + D, first = r;
-            for (int i = 0; i < j - 2; ++i, ++r) {
-                rm.tok[r] = yhat[i]; rm.pos[r] = n + i; rm.seq[r] = b; rm.kind[r] = i; rm.lim[r] = n;
-                rm.stg[r] = tile; rm.smask[r] = (1 << (i + 1)) - 1;
-            }
+            const int tile = stg0 + B + b * D + (j - 2), first = r;
+            const int common = (1 << (j - 2)) - 1;   // causal slots 0 .. j-3 of the causal tile
             for (int t = 0; t < D; ++t, ++r) {
-                rm.tok[r] = t == 0 ? yhat[j - 2] : mask_id; rm.pos[r] = n + j - 2 + t; rm.seq[r] = b; rm.kind[r] = j - 2 + t;
-                rm.lim[r] = n; rm.stg[r] = tile; rm.smask[r] = (1 << (causal ? j - 2 + t + 1 : ns)) - 1;
+                rm.tok[r] = t == 0 ? yhat[j - 2] : mask_id; rm.pos[r] = n + j - 2 + t; rm.seq[r] = b; rm.kind[r] = t;
+                rm.lim[r] = n; rm.stg[r] = tile; rm.stg2[r] = common ? ctile : -1;
+                rm.smask[r] = (int32_t)((uint32_t)((1 << (causal ? t + 1 : D)) - 1) | ((uint32_t)common << 16));
                 if (t == 0) rm.blk_row[b * (D - 1) + (j - 2)] = r;
             }
-            for (int o = 0; o < ns; o += gr, ++g) {
+            for (int o = 0; o < D; o += gr, ++g) {
                 rm.grp_row0[g] = first + o;
-                rm.grp_n[g] = min(gr, ns - o);
+                rm.grp_n[g] = min(gr, D - o);
                 rm.grp_seq[g] = b;
-                rm.grp_stg[g] = tile;
+                rm.grp_stg[g] = tile; rm.grp_stg2[g] = common ? ctile : -1;
             }
         }
     }
@@ -137,9 +148,9 @@ __global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mas
 
 int verify_rows_per_seq(int D, bool *shared_tile)
 {
-    const bool shared = (D - 2) + (D - 1) * D <= PAGE;   // every row of a sequence fits one staging tile
-    if (shared_tile) *shared_tile = shared;
-    return shared ? (D - 2) + (D - 1) * D : (D - 1) * D + (D - 2) * (D - 1) / 2;
+    if (D < 2) { if (shared_tile) *shared_tile = true; return 0; }
+    if (shared_tile) *shared_tile = (D - 2) + (D - 1) * D <= PAGE;   // every row of a sequence fits one staging tile
+    return (D - 2) + (D - 1) * D;
 }
 
 void launch_assemble_verify(hipStream_t s, const SeqState &st, const RowMeta &rm, int B, int D, int mask_id, int group_rows,
@@ -437,7 +448,7 @@ void launch_rope_scatter(hipStream_t s, int dtype, const float *qkv, int n_slabs
 
 // ------------------------------------------------------------------------------------------------ attention
 // One wavefront per (row, query head).  Keys: the cache positions [0, lim) of the row's sequence and the slots of
-// the row's staging tile named by its slot mask; for a block row these are the D keys of its block (mask equation, Sec. 3.3:
+// the row's staging tiles named by its slot masks; for a block row these are the D keys of its block (mask equation, Sec. 3.3:
 // causal below the block start, full mutual attention inside the block).  Each lane walks a strided subset of the keys with a running
 // (max, sum, output); the 64 partial results are merged at the end.
 template <typename T, int HD>
@@ -447,9 +458,11 @@ __global__ __launch_bounds__(64) void attn_generic_k(const T *q, T *out, const T
     const int r = blockIdx.y;
     if (r >= rm.counts[0]) return;
     const int hq = blockIdx.x, G = Hq / kg.n_kv_heads, hk = hq / G, lane = threadIdx.x;
-    const int b = rm.seq[r], lim = rm.lim[r], stg = rm.stg[r];
-    const uint32_t smask = stg >= 0 ? (uint32_t)rm.smask[r] : 0u;
-    const int total = lim + (smask ? 32 - __clz(smask) : 0);   // key index lim + i stands for staging slot i
+    const int b = rm.seq[r], lim = rm.lim[r], stg = rm.stg[r], stg2 = rm.stg2[r];
+    const uint32_t sm_all = (uint32_t)rm.smask[r];
+    const uint32_t smask = stg >= 0 ? sm_all & 0xffffu : 0u, smask2 = stg2 >= 0 ? sm_all >> 16 : 0u;
+    // key index lim + i stands for slot i of the second staging tile (i < 16), lim + 16 + i for slot i of the row's own tile
+    const int total = lim + (smask ? 16 + 32 - __clz(smask) : (smask2 ? 32 - __clz(smask2) : 0));
     __shared__ float qs[HD];
     __shared__ float part[64][HD + 1];
     const float scale = 1.0f / sqrtf((float)HD);
@@ -461,7 +474,8 @@ __global__ __launch_bounds__(64) void attn_generic_k(const T *q, T *out, const T
     for (int j = lane; j < total; j += 64) {
         int page, slot;
         if (j < lim) { page = st.page_table[(size_t)b * kg.pages_per_seq + j / PAGE]; slot = j % PAGE; }
-        else { page = stg; slot = j - lim; if (!((smask >> slot) & 1u)) continue; }
+        else if (j < lim + 16) { page = stg2; slot = j - lim; if (!((smask2 >> slot) & 1u)) continue; }
+        else { page = stg; slot = j - lim - 16; if (!((smask >> slot) & 1u)) continue; }
         const T *Kb = pool + kg.tile(page, hk), *Vb = Kb + PAGE * HD;
         float sdot = 0.f;
 #pragma unroll

@@ -127,19 +127,19 @@ void plan(const sdlm_model_cfg *m, const sdlm_run_cfg *r, Layout *L)
     L->rope = take((size_t)max_pos * (d / 2) * sizeof(float2));
     L->pages_per_seq = (r->max_seq_len + PAGE - 1) / PAGE;
     L->n_pages = r->kv_layout == 0 ? r->max_batch * L->pages_per_seq : r->n_pages;
-    L->pool_tiles = L->n_pages + r->max_batch * r->block_D;   // pages, then one staging tile per sequence and per verification input
+    L->pool_tiles = L->n_pages + r->max_batch * (r->block_D + 1);   // pages, then per sequence: the step's staging tile, one per verification input, one for their shared causal rows
     L->pool = take((size_t)m->n_layers * L->pool_tiles * m->n_kv_heads * 2 * PAGE * d * e);
     const int B = r->max_batch, D = r->block_D;
     int pre = r->prefill_rows > 0 ? r->prefill_rows : 4096;   // measured on the 7B shape: 2048 rows/pass 66k tokens/s, 4096 72k, 8192 73k
     L->prefill_rows = pre;
-    L->verify_rows = B * ((D - 1) * D + (D - 2) * (D - 1) / 2);
+    L->verify_rows = B * verify_rows_per_seq(D, nullptr);
     L->max_rows = B * 2 * D > pre ? B * 2 * D : pre;
     if (L->verify_rows > L->max_rows) L->max_rows = L->verify_rows;
     L->max_rows = (L->max_rows + 63) / 64 * 64;
     L->max_groups = L->max_rows;   // worst case: every row its own group (prefill of many 1-token prompts)
     L->state_ints = (size_t)B * 3 + (size_t)B * D + (size_t)B * L->pages_per_seq + B + 4 + (size_t)B * D + B;
     L->state_i32 = take(L->state_ints * 4);
-    L->meta_ints = (size_t)L->max_rows * 7 + (size_t)L->max_groups * 4 + (size_t)B * D + 4;
+    L->meta_ints = (size_t)L->max_rows * 8 + (size_t)L->max_groups * 5 + (size_t)B * D + 4;
     L->meta_i32 = take(L->meta_ints * 4);
     const size_t R = L->max_rows;
     L->x = take(R * h * 4);
@@ -417,9 +417,9 @@ int sdlm_create(const sdlm_model_cfg *m, const sdlm_run_cfg *r, void *workspace,
     int32_t *mi = (int32_t *)(ws + L.meta_i32);
     c->rm.tok = mi; mi += L.max_rows; c->rm.pos = mi; mi += L.max_rows; c->rm.seq = mi; mi += L.max_rows;
     c->rm.kind = mi; mi += L.max_rows; c->rm.lim = mi; mi += L.max_rows;
-    c->rm.stg = mi; mi += L.max_rows; c->rm.smask = mi; mi += L.max_rows;
+    c->rm.stg = mi; mi += L.max_rows; c->rm.smask = mi; mi += L.max_rows; c->rm.stg2 = mi; mi += L.max_rows;
     c->rm.grp_row0 = mi; mi += L.max_groups; c->rm.grp_n = mi; mi += L.max_groups; c->rm.grp_seq = mi; mi += L.max_groups;
-    c->rm.grp_stg = mi; mi += L.max_groups;
+    c->rm.grp_stg = mi; mi += L.max_groups; c->rm.grp_stg2 = mi; mi += L.max_groups;
     c->rm.blk_row = mi; mi += (size_t)B * D;
     c->rm.counts = mi; mi += 4;
     c->x = (float *)(ws + L.x); c->xn = ws + L.xn; c->qkv = (float *)(ws + L.qkv); c->q = ws + L.q; c->att = ws + L.att;
@@ -577,6 +577,8 @@ int sdlm_prefill(sdlm_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
         int32_t counts[4] = {R, (int32_t)g0.size(), 0, c->L.mfma ? mfma_attn_chunk_floor(&c->m, c->r.max_seq_len, (int)g0.size(), c->L.attn_bytes) : 0};
         const std::vector<int32_t> none((size_t)R, -1), zero((size_t)R, 0);   // causal rows: no staging tile
         HIPCHK(c, hipMemcpyAsync(c->rm.stg, none.data(), R * 4, hipMemcpyHostToDevice, s));
+        HIPCHK(c, hipMemcpyAsync(c->rm.stg2, none.data(), R * 4, hipMemcpyHostToDevice, s));
+        HIPCHK(c, hipMemcpyAsync(c->rm.grp_stg2, none.data(), g0.size() * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.smask, zero.data(), R * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.grp_stg, none.data(), g0.size() * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.tok, tok.data(), R * 4, hipMemcpyHostToDevice, s));
@@ -706,7 +708,6 @@ int sdlm_verify_step(sdlm_ctx *c, int32_t rule, int32_t *ids_tilde, int32_t *cou
     if (!c->stepped) return fail(c, SDLM_ESTATE, "verify_step without a preceding decode_step");
     if (rule != 0 && rule != 1) return fail(c, SDLM_EINVAL, "verify rule %d is not 0 (agreeing prefix) or 1 (largest agreeing index)", rule);
     const int B = c->batch, D = c->r.block_D;
-    if (2 * D - 2 > PAGE) return fail(c, SDLM_EINVAL, "verification needs 2D-2 <= %d staging slots; block_D is %d", PAGE, D);
     hipStream_t s = c->stream;
     if (D >= 2) {
         // positions reach n + 2D - 3 <= max_seq_len + D - 3 (decode_step checked n + D <= max_seq_len): inside the rotary
@@ -716,8 +717,7 @@ int sdlm_verify_step(sdlm_ctx *c, int32_t rule, int32_t *ids_tilde, int32_t *cou
         const int rows = B * rows_seq;
         const int gr = c->L.group_rows;
         int groups = 0;
-        if (shared) groups = (rows_seq + gr - 1) / gr;
-        else for (int j = 2; j <= D; ++j) groups += (j - 2 + D + gr - 1) / gr;
+        groups = verify_groups_per_seq(D, gr);
         const int cp_floor = c->L.mfma ? mfma_attn_chunk_floor(&c->m, c->r.max_seq_len, B * groups, c->L.attn_bytes) : 0;
         { Phase p(c, SDLM_PH_ROWS); launch_assemble_verify(s, c->st, c->rm, B, D, c->m.mask_token_id, gr, c->kg.staging_base, c->m.block_causal, c->m.n_kv_heads, cp_floor); }
         run_layers(c, rows, B * groups, rows);

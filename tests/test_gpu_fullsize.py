@@ -373,31 +373,28 @@ def test_fullsize_verify_is_the_next_steps_first_prediction(name):
     torch.cuda.synchronize()
     ctx.tap(0, -1, None)
     yh, yt, g = yhat.cpu().numpy(), ytil.cpu().numpy(), gv.cpu().numpy()
-    # --- the verification rows.  Input j = 2..D is yhat^1..yhat^{j-2} causal, then the block [yhat^{j-1}, m..].  When the
-    # D-2 distinct causal rows and the (D-1) D block rows of a sequence fit the 16 slots of one staging tile (D <= 4), the
-    # causal rows come once, first, and the blocks follow; otherwise every input is a run of its own with its own tile.
+    # --- the verification rows of a sequence: its D-2 causal rows yhat^1..yhat^{D-2} once, then for every input j = 2..D
+    # the block [yhat^{j-1}, m..].  When all of them fit the 16 slots of one staging tile (D <= 4) the block of input j
+    # sits in slots D-2 + (j-2) D ...; otherwise the causal rows and every block have a tile of their own (slots from 0).
     vrows = ctx.rows()
     shared = (D - 2) + (D - 1) * D <= 16
-    rows_seq = (D - 2) + (D - 1) * D if shared else (D - 1) * D + (D - 2) * (D - 1) // 2
+    rows_seq = (D - 2) + (D - 1) * D
     assert len(vrows["tok"]) == B * rows_seq
     first_row = {}
     r0 = 0
     for b in range(B):
-        if shared:
-            k = D - 2
-            assert vrows["tok"][r0:r0 + k].tolist() == [int(x) for x in yh[b, :k]]
-            assert vrows["pos"][r0:r0 + k].tolist() == list(range(n0[b], n0[b] + k)) and vrows["kind"][r0:r0 + k].tolist() == list(range(k))
-            r0 += k
+        k = D - 2
+        assert vrows["tok"][r0:r0 + k].tolist() == [int(x) for x in yh[b, :k]]
+        assert vrows["pos"][r0:r0 + k].tolist() == list(range(n0[b], n0[b] + k)) and vrows["kind"][r0:r0 + k].tolist() == list(range(k))
+        r0 += k
         for j in range(2, D + 1):
-            lead = 0 if shared else j - 2
-            want_tok = [int(x) for x in yh[b, :lead]] + [int(yh[b, j - 2])] + [m.mask_token_id] * (D - 1)
-            want_pos = list(range(n0[b], n0[b] + lead)) + list(range(n0[b] + j - 2, n0[b] + j - 2 + D))
-            k = lead + D
+            want_tok = [int(yh[b, j - 2])] + [m.mask_token_id] * (D - 1)
+            want_pos = list(range(n0[b] + j - 2, n0[b] + j - 2 + D))
             slot0 = (D - 2) + (j - 2) * D if shared else 0
-            assert vrows["tok"][r0:r0 + k].tolist() == want_tok and vrows["pos"][r0:r0 + k].tolist() == want_pos
-            assert vrows["kind"][r0:r0 + k].tolist() == list(range(slot0, slot0 + k))
-            first_row[(b, j)] = r0 + lead
-            r0 += k
+            assert vrows["tok"][r0:r0 + D].tolist() == want_tok and vrows["pos"][r0:r0 + D].tolist() == want_pos
+            assert vrows["kind"][r0:r0 + D].tolist() == list(range(slot0, slot0 + D))
+            first_row[(b, j)] = r0
+            r0 += D
         assert vrows["seq"][r0 - rows_seq:r0].eq(b).all()
     assert np.array_equal(yt[:, 0], yh[:, 0])
     for b in range(B):

@@ -319,11 +319,13 @@ def test_bf16_mfma_entropy_confidence():
 
 
 # ------------------------------------------------------------------ self-speculative verification (Sec. 3.4, Eq. 10)
-@pytest.mark.parametrize("D,rule,paged", [(2, 0, False), (3, 1, True), (4, 0, True), (4, 1, False), (5, 0, False), (6, 0, True), (9, 1, False)])
+@pytest.mark.parametrize("D,rule,paged", [(2, 0, False), (3, 1, True), (4, 0, True), (4, 1, False), (5, 0, False), (6, 0, True), (8, 0, False),
+                                          (9, 1, False), (10, 0, True), (12, 1, False), (16, 0, True)])
 def test_verify_small_fp32(D, rule, paged):
     """Second pass of a self-speculative step against the oracle's: logits of every verification input, ytilde,
-    gamma_verify bit-exact, and the verified count is what an argument-less commit publishes.  D <= 4: the rows of a
-    sequence share one staging tile and its causal rows are computed once; D >= 5: one tile per input."""
+    gamma_verify bit-exact, and the verified count is what an argument-less commit publishes.  The causal rows of the
+    speculative tokens are computed once per sequence; D <= 4: all rows of a sequence share one staging tile, D >= 5: the
+    causal rows and every input's block have tiles of their own and a block row reads two of them."""
     m = gpu_cfg()
     om, g_dev, layers_dev = both_models(m, seed=6, std=0.3)
     lens = [1, 2, 15, 16, 17, 33]
@@ -407,13 +409,6 @@ def test_verify_error_paths():
     with pytest.raises(SdlmError):
         ctx.verify_step(0)              # the step has been committed
     ctx.close()
-    ctx = gpu_context(m, g_dev, layers_dev, max_batch=1, max_seq_len=96, D=10, tau=0.5)
-    ctx.prefill([np.array([1, 2, 3], dtype=np.int32)])
-    ids = torch.empty(1, 10, dtype=torch.int32, device="cuda")
-    ctx.decode_step(ids, cnt)
-    with pytest.raises(SdlmError):
-        ctx.verify_step(0)              # 2D-2 staging slots do not fit a 16-slot tile
-    ctx.close()
 
 
 @pytest.mark.parametrize("name,kw,lens,D", [
@@ -422,7 +417,9 @@ def test_verify_error_paths():
     ("vg8-D8-two-groups-per-input", dict(n_q_heads=16, n_kv_heads=2, hidden=512), [5, 130, 300], 8),
     ("vg16-four-groups-across-inputs", dict(n_q_heads=16, n_kv_heads=1, hidden=256), [2, 31, 90], 4),
     ("vg4-D3", dict(n_q_heads=8, n_kv_heads=2), [7, 16, 49], 3),
-    ("vg3-D5-tile-per-input", dict(n_q_heads=6, n_kv_heads=2), [4, 40], 5),
+    ("vg3-D5-two-staging-tiles", dict(n_q_heads=6, n_kv_heads=2), [4, 40], 5),
+    ("vg7-D9", dict(n_q_heads=14, n_kv_heads=2, vocab=1000, ffn=320), [3, 70], 9),
+    ("vg4-D16", dict(n_q_heads=8, n_kv_heads=2), [1, 33, 200], 16),
 ])
 def test_verify_bf16_mfma(name, kw, lens, D):
     m = mfma_cfg(**kw)
@@ -631,7 +628,7 @@ def test_bf16_mfma_random_shapes(seed):
     ctx = gpu_context(m, g_dev, layers_dev, max_batch=len(lens), max_seq_len=max_len, D=D, tau=0.5, paged=paged, n_pages=n_pages,
                       prefill_rows=int(np.random.RandomState(seed).choice([32, 64, 200])))
     assert ctx.kernel_info == "mfma-bf16"
-    verify = 0 if (2 <= D <= 5 and seed % 2 == 0) else None
+    verify = 0 if (D >= 2 and seed % 2 == 0) else None
     st, _ = lockstep(ctx, om, prompts, D, 0.5, steps, logit_tol=2e-2, conf_tol=1e-3, overrides=ovr, bf16=True, max_len=max_len,
                      verify_rule=verify)
     print(f"random shape {seed}: {kw} B={len(lens)} D={D} paged={paged} verify={verify}", st)
@@ -661,7 +658,7 @@ def test_fp32_generic_random_shapes(seed):
     n_pages = sum((n + steps * D + 15) // 16 + 1 for n in lens)
     ctx = gpu_context(m, g_dev, layers_dev, max_batch=B, max_seq_len=max_len, D=D, tau=0.5, paged=paged, n_pages=n_pages,
                       prefill_rows=int(rng.choice([16, 64, 200])))
-    verify = int(rng.randint(0, 2)) if 2 <= D <= 9 and seed % 2 == 0 else None
+    verify = int(rng.randint(0, 2)) if D >= 2 and seed % 2 == 0 else None
     st, _ = lockstep(ctx, om, prompts, D, 0.5, steps, logit_tol=1e-4, conf_tol=1e-5, overrides=ovr, max_len=max_len, verify_rule=verify)
     print(f"random fp32 shape {seed}: B={B} D={D} d={d} paged={paged} verify={verify}", st)
     assert st.id_near_tie == 0
