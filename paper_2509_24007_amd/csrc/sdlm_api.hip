@@ -261,7 +261,8 @@ void run_taps(sdlm_ctx *c, int layer, int which, const void *src, size_t bytes)
 
 // The decoder layers over the rows described by c->rm.  `rows` bounds the launch grids (the device-side row
 // count decides what is computed); `rows_sure` is a host-known lower bound of that count (it only steers launch shapes).
-void run_layers(sdlm_ctx *c, int rows, int groups, int rows_sure)
+// `cache_only`: the pass only has to leave its rows' K/V in the cache (prefill): the last layer then ends after the K/V placement.
+void run_layers(sdlm_ctx *c, int rows, int groups, int rows_sure, bool cache_only)
 {
     const sdlm_model_cfg &m = c->m;
     const int dt = m.dtype, h = m.hidden, F = m.ffn, d = m.head_dim;
@@ -286,6 +287,7 @@ void run_layers(sdlm_ctx *c, int rows, int groups, int rows_sure)
             launch_rope_scatter(s, dt, qkv_slabs > 1 ? c->slabs : c->qkv, qkv_slabs, (size_t)rows * nqkv, c->q, pool_l, c->kg, c->rm, c->st, c->rope, m.n_q_heads, rows, rows_sure);
         }
         run_taps(c, l, 5, c->q, (size_t)rows * nq * e);
+        if (cache_only && l == m.n_layers - 1 && c->taps.empty()) break;   // nothing downstream of the last layer's K/V is used
         bool merge = false;
         {
             Phase p(c, SDLM_PH_ATTN);
@@ -590,7 +592,7 @@ int sdlm_prefill(sdlm_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
         HIPCHK(c, hipMemcpyAsync(c->rm.grp_n, gn.data(), gn.size() * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.grp_seq, gs.data(), gs.size() * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.counts, counts, sizeof counts, hipMemcpyHostToDevice, s));
-        run_layers(c, R, (int)g0.size(), R);
+        run_layers(c, R, (int)g0.size(), R, true);
         HIPCHK(c, hipStreamSynchronize(s));   // the host vectors are reused
         tok.clear(); pos.clear(); seq.clear(); kind.clear(); lim.clear(); g0.clear(); gn.clear(); gs.clear();
         return SDLM_OK;
@@ -632,7 +634,7 @@ static int decode_step_impl(sdlm_ctx *c, int32_t *ids, int32_t *count, float *co
         const int rows = B * 2 * D, groups = B * ((2 * D + c->L.group_rows - 1) / c->L.group_rows);
         const int cp_floor = c->L.mfma ? mfma_attn_chunk_floor(&c->m, c->r.max_seq_len, groups, c->L.attn_bytes) : 0;
         { Phase p(c, SDLM_PH_ROWS); launch_assemble_decode(s, c->st, c->rm, B, D, c->m.mask_token_id, c->L.group_rows, c->kg.staging_base, c->m.block_causal, c->m.n_kv_heads, cp_floor); }
-        run_layers(c, rows, groups, B * (D + (c->committed ? 1 : 0)));   // after a commit every sequence has >= 1 pending row
+        run_layers(c, rows, groups, B * (D + (c->committed ? 1 : 0)), false);   // after a commit every sequence has >= 1 pending row
         run_lm_head(c, B * D, logits);
         { Phase p(c, SDLM_PH_ACCEPT); launch_accept(s, c->st, c->ids_rows, c->conf_rows, B, D, c->r.tau, c->r.accept_rule, ids, count, conf); }
     };
@@ -720,7 +722,7 @@ int sdlm_verify_step(sdlm_ctx *c, int32_t rule, int32_t *ids_tilde, int32_t *cou
         groups = verify_groups_per_seq(D, gr);
         const int cp_floor = c->L.mfma ? mfma_attn_chunk_floor(&c->m, c->r.max_seq_len, B * groups, c->L.attn_bytes) : 0;
         { Phase p(c, SDLM_PH_ROWS); launch_assemble_verify(s, c->st, c->rm, B, D, c->m.mask_token_id, gr, c->kg.staging_base, c->m.block_causal, c->m.n_kv_heads, cp_floor); }
-        run_layers(c, rows, B * groups, rows);
+        run_layers(c, rows, B * groups, rows, false);
         run_lm_head(c, B * (D - 1), logits);
     }
     { Phase p(c, SDLM_PH_ACCEPT); launch_verify_accept(s, c->st, c->ids_rows, B, D, rule, ids_tilde, count); }

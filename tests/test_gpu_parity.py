@@ -343,6 +343,42 @@ def test_verify_small_fp32(D, rule, paged):
     ctx.close()
 
 
+@pytest.mark.parametrize("paged,prefill_rows", [(True, 256), (False, 4096)])
+def test_long_prefill_cache_matches_oracle_cache_bf16(paged, prefill_rows):
+    """Prefill of long prompts on the matrix-core path (several passes when prefill_rows is below the prompt length,
+    several KV chunks per attention work item, ragged last groups): every cached K and V vector of every layer, kv head
+    and position against the oracle's cache, which by its pins holds the K/V of the real tokens under causal attention
+    (Sec. 3.3: every block sees the real tokens before it causally).  The layers' inputs differ by bf16 rounding, so
+    the comparison is per vector, relative to the vector's largest entry."""
+    m = mfma_cfg(n_layers=3, n_q_heads=14, n_kv_heads=2, hidden=256, ffn=512)
+    om, g_dev, layers_dev = both_models(m, seed=31, std=0.05)
+    lens = [700, 1, 333, 1025]
+    prompts = [syn.uniform_int(31, f"lp{i}", n, 0, m.vocab - 1).numpy() for i, n in enumerate(lens)]
+    D = 4
+    n_pages = sum((n + 2 * D + 15) // 16 + 1 for n in lens)
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=len(lens), max_seq_len=max(lens) + 2 * D, D=D, tau=0.5, paged=paged,
+                      n_pages=n_pages if paged else 0, prefill_rows=prefill_rows)
+    assert ctx.kernel_info == "mfma-bf16"
+    ctx.prefill(prompts)
+    n, c = ctx.get_lengths()
+    assert n.tolist() == lens and c.tolist() == lens
+    worst_k = worst_v = 0.0
+    for b, p in enumerate(prompts):
+        s = orc.Seq(om, len(p) + 2 * D)
+        s.prefill(p)
+        for layer in range(m.n_layers):
+            for hk in range(m.n_kv_heads):
+                k, v = ctx.read_kv(layer, b, hk, 0, len(p))
+                k, v = k.numpy().astype(np.float64), v.numpy().astype(np.float64)
+                for pos in range(len(p)):
+                    ko, vo = s.read_kv(layer, pos, hk)
+                    worst_k = max(worst_k, float(np.max(np.abs(k[pos] - ko)) / np.max(np.abs(ko))))
+                    worst_v = max(worst_v, float(np.max(np.abs(v[pos] - vo)) / np.max(np.abs(vo))))
+    print(f"long prefill paged={paged} rows/pass={prefill_rows}: worst relative K error {worst_k:.3e}, V {worst_v:.3e}")
+    assert worst_k <= 2e-2 and worst_v <= 2e-2
+    ctx.close()
+
+
 def test_verify_position_independent_model_accepts_whole_block():
     """All-zero weights: every logit row is constant, arg-max is token 0 everywhere, so every position verifies."""
     m = gpu_cfg()
