@@ -42,6 +42,9 @@ struct AttnArgs {
 
 union Op8 { bf16x8 v; uint4 u; uint2 h[2]; uint32_t w[4]; };
 
+// TWO_STG: row groups may read a second staging tile (verification passes of block sizes above 4); decode steps and
+// prefill passes use the variant without it, which keeps the kernel at four workgroups per compute unit without spills.
+template <bool TWO_STG>
 __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
 {
     const int g = blockIdx.x, hk = blockIdx.y, chunk = blockIdx.z;
@@ -77,7 +80,7 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
     const int n_cache = c1 - c0;
     // Staging tiles follow the cache tiles of chunk 0: first the group's second tile (if a row sees it: upper half of
     // the slot masks), then its own tile (lower half).
-    const bool has1 = (any_blk & 0xffff) != 0, has2 = ((uint32_t)any_blk >> 16) != 0;
+    const bool has1 = (any_blk & 0xffff) != 0, has2 = TWO_STG && ((uint32_t)any_blk >> 16) != 0;
     const int nv = n_cache + (chunk == 0 ? (int)has1 + (int)has2 : 0);   // virtual tiles of this chunk; the last ones may be staging
     const int n_pairs = (nv + 1) / 2;
 
@@ -87,7 +90,9 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
     const bool wave_active = wave * 16 < QR;
     const int rl = qvalid ? qi / G : 0, hg = qvalid ? qi % G : 0, qrow = row0 + rl;
     const int lim_q = qvalid ? a.rm.lim[qrow] : 0;
-    const uint32_t smask_q = qvalid ? (uint32_t)a.rm.smask[qrow] : 0u;   // staging slots this query sees
+    // staging slots this query sees, re-packed by virtual tile: low half for tile n_cache, high half for tile n_cache + 1
+    const uint32_t smask_raw = qvalid ? (uint32_t)a.rm.smask[qrow] : 0u;
+    const uint32_t smask_q = has2 ? (smask_raw >> 16) | (smask_raw << 16) : smask_raw & 0xffffu;   // !TWO_STG: the tile's own mask
     Op8 qop[4];
     {
         const bf16_t *qp = a.q + ((size_t)qrow * a.Hq + hk * G + hg) * HD + lg * 8;
@@ -106,8 +111,8 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
     // through LDS in the cache's own operand order; two LDS buffers, the next two pairs ride in registers meanwhile.
     __shared__ __attribute__((aligned(16))) bf16_t kv[2][2][2 * PAGE * HD];   // [buffer][tile A/B][K block | V block]
     const size_t tile_elems = 2 * PAGE * HD;
-    const int stg_page = max(a.rm.grp_stg[g], 0), stg2_page = max(a.rm.grp_stg2[g], 0);
-    auto stg_of = [&](int u) { return (has2 && u == n_cache) ? stg2_page : stg_page; };   // staging tile behind virtual tile u >= n_cache
+    const int stg_last = max(a.rm.grp_stg[g], 0), stg_first = (TWO_STG && has2) ? max(a.rm.grp_stg2[g], 0) : stg_last;
+    auto stg_of = [&](int u) { return (TWO_STG && u == n_cache) ? stg_first : stg_last; };   // staging tile behind virtual tile u >= n_cache
     u32x4 rA[4], rB[4];   // two tile pairs in flight: the next one and the one after it
     auto fetch_pages = [&](int pgA, int pgB, u32x4 (&r)[4]) {
         const bf16_t *tA = a.pool + ((size_t)pgA * a.kg.n_kv_heads + hk) * tile_elems;
@@ -155,9 +160,9 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
             const bool fullB = hasB && !stgB && (c0 + uB + 1) * PAGE <= min_lim;
             if (!(fullA && fullB)) {
                 const int keyA = (c0 + uA) * PAGE + lg * 4, keyB = (c0 + uB) * PAGE + lg * 4;
-                // slot masks of the staging tile behind A / B: the second tile's are the upper half of the row's mask
-                const uint32_t mA = (has2 && uA == n_cache) ? smask_q >> 16 : smask_q & 0xffffu;
-                const uint32_t mB = (has2 && uB == n_cache) ? smask_q >> 16 : smask_q & 0xffffu;
+                // slot masks of the staging tile behind A / B
+                const uint32_t mA = TWO_STG ? (smask_q >> (uA == n_cache ? 0 : 16)) & 0xffffu : smask_q;
+                const uint32_t mB = TWO_STG ? (smask_q >> (uB == n_cache ? 0 : 16)) & 0xffffu : smask_q;
 #pragma unroll
                 for (int v = 0; v < 4; ++v) {
                     bool visA = stgA ? ((mA >> (lg * 4 + v)) & 1u) != 0 : (keyA + v < lim_q);
@@ -377,7 +382,7 @@ size_t mfma_attn_scratch_bytes(const sdlm_model_cfg *m, const sdlm_run_cfg *r, i
 
 bool launch_attn_mfma(hipStream_t s, const sdlm_model_cfg *m, int max_seq_len, const void *q, void *out, const void *pool_layer,
                       const KvGeom &kg, const RowMeta &rm, const SeqState &st, int D, int max_groups, void *scratch, size_t scratch_bytes,
-                      int part)
+                      int part, bool two_staging)
 {
     AttnArgs a;
     a.q = (const bf16_t *)q; a.out = (bf16_t *)out; a.pool = (const bf16_t *)pool_layer;
@@ -388,7 +393,10 @@ bool launch_attn_mfma(hipStream_t s, const sdlm_model_cfg *m, int max_seq_len, c
     a.part_ml = (float2 *)((char *)scratch + items * QMAX * HD * 4);
     a.c = 1.4426950408889634f / sqrtf((float)HD);
     a.early = (long)max_groups * kg.n_kv_heads * NQ <= 4096;
-    if (part == 0) hipLaunchKernelGGL(attn_mfma_k, dim3(max_groups, kg.n_kv_heads, a.max_chunks), dim3(256), 0, s, a);
+    if (part == 0) {
+        if (two_staging) hipLaunchKernelGGL(attn_mfma_k<true>, dim3(max_groups, kg.n_kv_heads, a.max_chunks), dim3(256), 0, s, a);
+        else hipLaunchKernelGGL(attn_mfma_k<false>, dim3(max_groups, kg.n_kv_heads, a.max_chunks), dim3(256), 0, s, a);
+    }
     else if (a.max_chunks > 1) hipLaunchKernelGGL(attn_combine_k, dim3(max_groups, kg.n_kv_heads, NQ), dim3(256), 0, s, a);
     return a.max_chunks > 1;
 }

@@ -59,8 +59,9 @@ __host__ __device__ inline int k_off(int slot, int i) { return (i >> 3) * (PAGE 
 __host__ __device__ inline int v_off(int slot, int i) { return (((i >> 4) << 2) + (slot >> 2)) * 64 + ((i & 15) << 2) + (slot & 3); }
 
 // Tiles per KV chunk for an attention launch whose (row group, kv head) items cover `item_pages` 16-key tiles in all:
-// large enough that the launch has about 2.25 work items per compute unit (measured on the 7B and 32B shapes: all work
-// items resident at once, two to three per unit, is the fastest split; finer chunks only add partial results to merge),
+// large enough that the launch has about 2.25 work items per compute unit (measured by whole-step time on the 7B and 32B
+// shapes, batch 64 and 32: all work items resident at once, two to three per unit, is the fastest split; finer chunks
+// add partial results to merge, coarser ones leave the units unevenly loaded),
 // a multiple of 8, and never below `floor_pages` (the host's bound: partial-result scratch, 64 chunks per item).
 __host__ __device__ inline int attn_chunk_pages(long item_pages, int floor_pages)
 {

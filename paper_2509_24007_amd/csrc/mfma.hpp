@@ -31,10 +31,11 @@ void mfma_gemm_plan(int epi, int rows, int min_rows, int N, int K, size_t slab_r
 // defer_reduce, in which case the next RMSNorm adds them (slab stride = a.max_rows * a.N floats).
 int launch_gemm_mfma(hipStream_t s, int epi, const GemmArgs &a, float *slabs, size_t slab_room_floats, bool defer_reduce);
 // part 0: the attention kernel; part 1: the merge of the split-KV partials (a no-op when the launch has a single
-// chunk).  Returns whether the launch shape needs the merge.
+// chunk).  Returns whether the launch shape needs the merge.  two_staging: row groups of this pass may read a second
+// staging tile (a verification pass whose rows do not fit one tile).
 bool launch_attn_mfma(hipStream_t s, const sdlm_model_cfg *m, int max_seq_len, const void *q, void *out, const void *pool_layer,
                       const KvGeom &kg, const RowMeta &rm, const SeqState &st, int D, int max_groups, void *scratch, size_t scratch_bytes,
-                      int part);
+                      int part, bool two_staging);
 void launch_lmhead_mfma(hipStream_t s, const void *xhat, const void *w_packed, const int32_t *p_rows, int max_rows, int min_rows, int V, int h,
                         float scale, int conf_fn, float *logits_out, void *scratch, int32_t *ids, float *conf);
 

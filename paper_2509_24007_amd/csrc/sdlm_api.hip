@@ -262,7 +262,7 @@ void run_taps(sdlm_ctx *c, int layer, int which, const void *src, size_t bytes)
 // The decoder layers over the rows described by c->rm.  `rows` bounds the launch grids (the device-side row
 // count decides what is computed); `rows_sure` is a host-known lower bound of that count (it only steers launch shapes).
 // `cache_only`: the pass only has to leave its rows' K/V in the cache (prefill): the last layer then ends after the K/V placement.
-void run_layers(sdlm_ctx *c, int rows, int groups, int rows_sure, bool cache_only)
+void run_layers(sdlm_ctx *c, int rows, int groups, int rows_sure, bool cache_only, bool two_staging = false)
 {
     const sdlm_model_cfg &m = c->m;
     const int dt = m.dtype, h = m.hidden, F = m.ffn, d = m.head_dim;
@@ -291,12 +291,12 @@ void run_layers(sdlm_ctx *c, int rows, int groups, int rows_sure, bool cache_onl
         bool merge = false;
         {
             Phase p(c, SDLM_PH_ATTN);
-            if (c->L.mfma) merge = launch_attn_mfma(s, &c->m, c->r.max_seq_len, c->q, c->att, pool_l, c->kg, c->rm, c->st, c->r.block_D, groups, c->attn_part, c->L.attn_bytes, 0);
+            if (c->L.mfma) merge = launch_attn_mfma(s, &c->m, c->r.max_seq_len, c->q, c->att, pool_l, c->kg, c->rm, c->st, c->r.block_D, groups, c->attn_part, c->L.attn_bytes, 0, two_staging);
             else launch_attn_generic(s, dt, c->q, c->att, pool_l, c->kg, c->rm, c->st, m.n_q_heads, rows);
         }
         if (merge) {
             Phase p(c, SDLM_PH_ATTN_MERGE);
-            launch_attn_mfma(s, &c->m, c->r.max_seq_len, c->q, c->att, pool_l, c->kg, c->rm, c->st, c->r.block_D, groups, c->attn_part, c->L.attn_bytes, 1);
+            launch_attn_mfma(s, &c->m, c->r.max_seq_len, c->q, c->att, pool_l, c->kg, c->rm, c->st, c->r.block_D, groups, c->attn_part, c->L.attn_bytes, 1, two_staging);
         }
         run_taps(c, l, 1, c->att, (size_t)rows * nq * e);
         {
@@ -722,7 +722,7 @@ int sdlm_verify_step(sdlm_ctx *c, int32_t rule, int32_t *ids_tilde, int32_t *cou
         groups = verify_groups_per_seq(D, gr);
         const int cp_floor = c->L.mfma ? mfma_attn_chunk_floor(&c->m, c->r.max_seq_len, B * groups, c->L.attn_bytes) : 0;
         { Phase p(c, SDLM_PH_ROWS); launch_assemble_verify(s, c->st, c->rm, B, D, c->m.mask_token_id, gr, c->kg.staging_base, c->m.block_causal, c->m.n_kv_heads, cp_floor); }
-        run_layers(c, rows, B * groups, rows, false);
+        run_layers(c, rows, B * groups, rows, false, !shared);
         run_lm_head(c, B * (D - 1), logits);
     }
     { Phase p(c, SDLM_PH_ACCEPT); launch_verify_accept(s, c->st, c->ids_rows, B, D, rule, ids_tilde, count); }
