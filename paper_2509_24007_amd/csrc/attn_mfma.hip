@@ -37,7 +37,6 @@ struct AttnArgs {
     float *part_o;      // [item][QMAX][HD]
     float2 *part_ml;    // [item][QMAX]
     float c;            // log2(e) / sqrt(d)
-    bool early;         // merge kernel: request the first chunks' partials before the group is looked up
 };
 
 union Op8 { bf16x8 v; uint4 u; uint2 h[2]; uint32_t w[4]; };
@@ -246,29 +245,34 @@ __global__ __launch_bounds__(256, 4) void attn_mfma_k(AttnArgs a)
 // launch rather than "the last workgroup merges": the chunks run on different XCDs, whose L2s only agree at
 // kernel boundaries, and a device-scope fence in every workgroup costs more than this launch.
 // grid (group, kv head, 16-query tile); the tile's scale factors are computed once and shared through LDS.
-// The kernel is a chain of dependent memory round trips and little else, so everything whose address follows from the
-// block index alone (the first chunks' partial results and running maxima) is requested before the group is looked
-// up: the partial-result area covers max_chunks chunks for every (group, head) of the grid, and what is fetched for
-// chunks or queries that do not exist is never used.  Only worth it for the small grids of a decode step (a.early):
-// in a prefill pass most (group, head) items have a single chunk and the early requests would be wasted traffic.
+// The kernel is a chain of dependent memory round trips and little else, so the partial results are requested
+// before the group is looked up: the row assembly leaves, per group, how many chunks and rows it has (grp_hint), and
+// exactly those partial results and running maxima are requested one round trip in.  The hint only steers these early
+// requests: the chunk count that decides the result is derived from the rows' limits as in the attention kernel, and
+// what a hint misses is fetched afterwards.
 __global__ __launch_bounds__(256) void attn_combine_k(AttnArgs a)
 {
     constexpr int CU = 4, V4 = HD / 4, EPT = 16 * V4 / 256;   // chunks requested together; float4 per query; elements per thread
     const int g = blockIdx.x, hk = blockIdx.y, nq = blockIdx.z, tid = threadIdx.x, lane = tid & 63;
     const size_t item0 = ((size_t)g * a.kg.n_kv_heads + hk) * a.max_chunks;
+    const int hint = a.rm.grp_hint[g];   // in bounds for every group of the grid
     const int n_groups = a.rm.counts[1];
     const int cp = max(a.rm.counts[3], a.chunk_pages);
-    const int row0 = a.rm.grp_row0[g], nrows = a.rm.grp_n[g];   // in bounds for every group of the grid
+    const int row0 = a.rm.grp_row0[g], nrows = a.rm.grp_n[g];
+    const int hc = min(hint & 0xff, a.max_chunks), hq = ((hint >> 8) & 0xff) * a.G;   // chunks and queries to expect
     const int mq = tid & 15, mc = tid >> 4;
     float2 ml0 = make_float2(0.f, 0.f);
     f32x4 po[EPT][CU];
-    if (a.early) ml0 = a.part_ml[(item0 + min(mc, a.max_chunks - 1)) * QMAX + nq * 16 + mq];
+    const bool ml_early = hc > 1 && mc < hc;
+    if (ml_early) ml0 = a.part_ml[(item0 + mc) * QMAX + nq * 16 + mq];
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
-        if (!a.early) break;
         const int e = tid + j * 256, qi = nq * 16 + e / V4, d4 = (e % V4) * 4;
 #pragma unroll
-        for (int u = 0; u < CU; ++u) po[j][u] = *(const f32x4 *)(a.part_o + ((item0 + min(u, a.max_chunks - 1)) * QMAX + qi) * HD + d4);
+        for (int u = 0; u < CU; ++u) {
+            po[j][u] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (hc > 1 && u < hc && qi < hq) po[j][u] = *(const f32x4 *)(a.part_o + ((item0 + u) * QMAX + qi) * HD + d4);
+        }
     }
     if (g >= n_groups) return;
     const int QR = nrows * a.G;
@@ -280,7 +284,7 @@ __global__ __launch_bounds__(256) void attn_combine_k(AttnArgs a)
     if (n_chunks == 1) return;   // the attention kernel wrote the final result itself
     __shared__ float sf[16][65], sl[16][65];   // [query][chunk]: running maximum, then 2^{c(m_c - M)} / L; row sum
     for (int c = mc; c < n_chunks; c += 16) {
-        const float2 ml = (c < 16 && a.early) ? ml0 : a.part_ml[(item0 + c) * QMAX + nq * 16 + mq];
+        const float2 ml = (c < 16 && ml_early) ? ml0 : a.part_ml[(item0 + c) * QMAX + nq * 16 + mq];
         sf[mq][c] = ml.x;
         sl[mq][c] = ml.y;
     }
@@ -305,10 +309,10 @@ __global__ __launch_bounds__(256) void attn_combine_k(AttnArgs a)
         if (qi >= QR) continue;
         f32x4 o = {0.f, 0.f, 0.f, 0.f};
         for (int c0 = 0; c0 < n_chunks; c0 += CU) {
-            if (c0 > 0 || !a.early) {
 #pragma unroll
-                for (int u = 0; u < CU; ++u)
-                    po[j][u] = *(const f32x4 *)(a.part_o + ((item0 + min(c0 + u, n_chunks - 1)) * QMAX + qi) * HD + d4);
+            for (int u = 0; u < CU; ++u) {
+                const bool have = c0 == 0 && hc > 1 && u < hc && qi < hq;   // requested at the top
+                if (!have && c0 + u < n_chunks) po[j][u] = *(const f32x4 *)(a.part_o + ((item0 + c0 + u) * QMAX + qi) * HD + d4);
             }
 #pragma unroll
             for (int u = 0; u < CU; ++u)
@@ -392,7 +396,6 @@ bool launch_attn_mfma(hipStream_t s, const sdlm_model_cfg *m, int max_seq_len, c
     a.part_o = (float *)scratch;
     a.part_ml = (float2 *)((char *)scratch + items * QMAX * HD * 4);
     a.c = 1.4426950408889634f / sqrtf((float)HD);
-    a.early = (long)max_groups * kg.n_kv_heads * NQ <= 4096;
     if (part == 0) {
         if (two_staging) hipLaunchKernelGGL(attn_mfma_k<true>, dim3(max_groups, kg.n_kv_heads, a.max_chunks), dim3(256), 0, s, a);
         else hipLaunchKernelGGL(attn_mfma_k<false>, dim3(max_groups, kg.n_kv_heads, a.max_chunks), dim3(256), 0, s, a);

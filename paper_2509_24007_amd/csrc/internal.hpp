@@ -70,6 +70,12 @@ __host__ __device__ inline int attn_chunk_pages(long item_pages, int floor_pages
     return cp > floor_pages ? (int)cp : floor_pages;
 }
 
+__host__ __device__ inline int attn_group_hint(int max_lim, int rows, int chunk_pages)
+{
+    int pages = (max_lim + PAGE - 1) / PAGE, chunks = (pages + chunk_pages - 1) / chunk_pages;
+    return (chunks < 1 ? 1 : chunks > 255 ? 255 : chunks) | rows << 8;
+}
+
 // Packed description of the rows of one forward pass (device arrays).
 struct RowMeta {
     int32_t *tok, *pos, *seq, *kind, *lim;  // [max_rows]; kind: -1 = K/V go to the cache slot of pos, else the slot in the
@@ -80,6 +86,8 @@ struct RowMeta {
                                             // verification pass
     int32_t *grp_row0, *grp_n, *grp_seq;    // [max_groups]: runs of <= GROUP_ROWS rows of one sequence that share their staging tiles
     int32_t *grp_stg, *grp_stg2;            // [max_groups]: those tiles (-1: none)
+    int32_t *grp_hint;                      // [max_groups]: KV chunks of the group's attention work (bits 0..7) and its rows (bits 8..15); lets
+                                            // the merge kernel request exactly the partial results that exist before it has looked the group up
     int32_t *blk_row;                       // [max_batch*D]: packed row index of the rows that go through the LM head
     int32_t *counts;                        // [4]: rows R, groups, LM-head rows, tiles per KV chunk of the attention launch
 };

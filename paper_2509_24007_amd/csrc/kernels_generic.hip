@@ -12,7 +12,7 @@ namespace sdlm {
 // below position s = n-1 only; the causal copy of x_last at s is for later steps.
 __global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mask_id, int gr, int stg0, int causal, int Hkv, int cp_floor)
 {
-    __shared__ int row0[1025], grp0[1025];
+    __shared__ int row0[1025], grp0[1025], cp_s;
     if (threadIdx.x == 0) {
         int r = 0, g = 0;
         long tiles = 0;   // 16-key tiles the attention's work items stream, per kv head
@@ -24,7 +24,8 @@ __global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mas
             tiles += (long)ng * ((st.n[b] + PAGE - 1) / PAGE);
         }
         row0[B] = r; grp0[B] = g;
-        rm.counts[0] = r; rm.counts[1] = g; rm.counts[2] = B * D; rm.counts[3] = attn_chunk_pages(tiles * Hkv, cp_floor);
+        cp_s = attn_chunk_pages(tiles * Hkv, cp_floor);
+        rm.counts[0] = r; rm.counts[1] = g; rm.counts[2] = B * D; rm.counts[3] = cp_s;
     }
     __syncthreads();
     for (int b = threadIdx.x; b < B; b += blockDim.x) {
@@ -43,11 +44,15 @@ __global__ void assemble_decode_k(SeqState st, RowMeta rm, int B, int D, int mas
         }
         int rows = p + D, g = grp0[b];
         for (int o = 0; o < rows; o += gr, ++g) {
+            const int gn = min(gr, rows - o);
             rm.grp_row0[g] = row0[b] + o;
-            rm.grp_n[g] = min(gr, rows - o);
+            rm.grp_n[g] = gn;
             rm.grp_seq[g] = b;
             rm.grp_stg[g] = stg0 + b;
             rm.grp_stg2[g] = -1;
+            // largest visible-key limit of the group's rows: pending row i has c + i + 1, block rows n - 1
+            const int last = o + gn - 1, lim_max = o < p ? c + min(last, p - 1) + 1 : n - 1;
+            rm.grp_hint[g] = attn_group_hint(lim_max, gn, cp_s);
         }
     }
 }
@@ -76,7 +81,7 @@ void launch_assemble_decode(hipStream_t s, const SeqState &st, const RowMeta &rm
 //     upper half of its slot mask).  Row groups do not straddle inputs, so a group reads at most these two tiles.
 __global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mask_id, int gr, int stg0, int causal, int shared, int Hkv, int cp_floor)
 {
-    __shared__ int row0[1025], grp0[1025];
+    __shared__ int row0[1025], grp0[1025], cp_s;
     const int rows_seq = (D - 2) + (D - 1) * D;
     const int groups_seq = verify_groups_per_seq(D, gr);
     if (threadIdx.x == 0) {
@@ -86,7 +91,8 @@ __global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mas
             tiles += (long)groups_seq * ((st.n[b] + PAGE - 1) / PAGE);
         }
         rm.counts[0] = B * rows_seq; rm.counts[1] = B * groups_seq; rm.counts[2] = B * (D - 1);
-        rm.counts[3] = attn_chunk_pages(tiles * Hkv, cp_floor);
+        cp_s = attn_chunk_pages(tiles * Hkv, cp_floor);
+        rm.counts[3] = cp_s;
     }
     __syncthreads();
     for (int b = threadIdx.x; b < B; b += blockDim.x) {
@@ -112,6 +118,7 @@ __global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mas
                 rm.grp_n[g] = min(gr, rows_seq - o);
                 rm.grp_seq[g] = b;
                 rm.grp_stg[g] = tile; rm.grp_stg2[g] = -1;
+                rm.grp_hint[g] = attn_group_hint(n, min(gr, rows_seq - o), cp_s);
             }
             continue;
         }
@@ -126,6 +133,7 @@ __global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mas
             rm.grp_n[g] = min(gr, D - 2 - o);
             rm.grp_seq[g] = b;
             rm.grp_stg[g] = ctile; rm.grp_stg2[g] = -1;
+            rm.grp_hint[g] = attn_group_hint(n, min(gr, D - 2 - o), cp_s);
         }
         for (int j = 2; j <= D; ++j) {
             const int tile = stg0 + B + b * D + (j - 2), first = r;
@@ -141,6 +149,7 @@ __global__ void assemble_verify_k(SeqState st, RowMeta rm, int B, int D, int mas
                 rm.grp_n[g] = min(gr, D - o);
                 rm.grp_seq[g] = b;
                 rm.grp_stg[g] = tile; rm.grp_stg2[g] = common ? ctile : -1;
+                rm.grp_hint[g] = attn_group_hint(n, min(gr, D - o), cp_s);
             }
         }
     }

@@ -139,7 +139,7 @@ void plan(const sdlm_model_cfg *m, const sdlm_run_cfg *r, Layout *L)
     L->max_groups = L->max_rows;   // worst case: every row its own group (prefill of many 1-token prompts)
     L->state_ints = (size_t)B * 3 + (size_t)B * D + (size_t)B * L->pages_per_seq + B + 4 + (size_t)B * D + B;
     L->state_i32 = take(L->state_ints * 4);
-    L->meta_ints = (size_t)L->max_rows * 8 + (size_t)L->max_groups * 5 + (size_t)B * D + 4;
+    L->meta_ints = (size_t)L->max_rows * 8 + (size_t)L->max_groups * 6 + (size_t)B * D + 4;
     L->meta_i32 = take(L->meta_ints * 4);
     const size_t R = L->max_rows;
     L->x = take(R * h * 4);
@@ -421,7 +421,7 @@ int sdlm_create(const sdlm_model_cfg *m, const sdlm_run_cfg *r, void *workspace,
     c->rm.kind = mi; mi += L.max_rows; c->rm.lim = mi; mi += L.max_rows;
     c->rm.stg = mi; mi += L.max_rows; c->rm.smask = mi; mi += L.max_rows; c->rm.stg2 = mi; mi += L.max_rows;
     c->rm.grp_row0 = mi; mi += L.max_groups; c->rm.grp_n = mi; mi += L.max_groups; c->rm.grp_seq = mi; mi += L.max_groups;
-    c->rm.grp_stg = mi; mi += L.max_groups; c->rm.grp_stg2 = mi; mi += L.max_groups;
+    c->rm.grp_stg = mi; mi += L.max_groups; c->rm.grp_stg2 = mi; mi += L.max_groups; c->rm.grp_hint = mi; mi += L.max_groups;
     c->rm.blk_row = mi; mi += (size_t)B * D;
     c->rm.counts = mi; mi += 4;
     c->x = (float *)(ws + L.x); c->xn = ws + L.xn; c->qkv = (float *)(ws + L.qkv); c->q = ws + L.q; c->att = ws + L.att;
@@ -566,7 +566,7 @@ int sdlm_prefill(sdlm_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
     HIPCHK(c, hipStreamSynchronize(s));
     // causal passes over the prompts, prefill_rows rows at a time
     const int cap = c->L.prefill_rows;
-    std::vector<int32_t> tok, pos, seq, kind, lim, g0, gn, gs;
+    std::vector<int32_t> tok, pos, seq, kind, lim, g0, gn, gs, gh;
     auto flush = [&]() -> int {
         if (tok.empty()) return SDLM_OK;
         int R = (int)tok.size();
@@ -577,6 +577,8 @@ int sdlm_prefill(sdlm_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
             r0 = r1;
         }
         int32_t counts[4] = {R, (int32_t)g0.size(), 0, c->L.mfma ? mfma_attn_chunk_floor(&c->m, c->r.max_seq_len, (int)g0.size(), c->L.attn_bytes) : 0};
+        for (size_t g = 0; g < g0.size(); ++g)   // causal rows: the group's last row sees the most keys
+            gh.push_back(attn_group_hint(lim[g0[g] + gn[g] - 1], gn[g], counts[3] > 0 ? counts[3] : 1));
         const std::vector<int32_t> none((size_t)R, -1), zero((size_t)R, 0);   // causal rows: no staging tile
         HIPCHK(c, hipMemcpyAsync(c->rm.stg, none.data(), R * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.stg2, none.data(), R * 4, hipMemcpyHostToDevice, s));
@@ -591,10 +593,11 @@ int sdlm_prefill(sdlm_ctx *c, int32_t batch, const int32_t *ids, const int32_t *
         HIPCHK(c, hipMemcpyAsync(c->rm.grp_row0, g0.data(), g0.size() * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.grp_n, gn.data(), gn.size() * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.grp_seq, gs.data(), gs.size() * 4, hipMemcpyHostToDevice, s));
+        HIPCHK(c, hipMemcpyAsync(c->rm.grp_hint, gh.data(), gh.size() * 4, hipMemcpyHostToDevice, s));
         HIPCHK(c, hipMemcpyAsync(c->rm.counts, counts, sizeof counts, hipMemcpyHostToDevice, s));
         run_layers(c, R, (int)g0.size(), R, true);
         HIPCHK(c, hipStreamSynchronize(s));   // the host vectors are reused
-        tok.clear(); pos.clear(); seq.clear(); kind.clear(); lim.clear(); g0.clear(); gn.clear(); gs.clear();
+        tok.clear(); pos.clear(); seq.clear(); kind.clear(); lim.clear(); g0.clear(); gn.clear(); gs.clear(); gh.clear();
         return SDLM_OK;
     };
     for (int b = 0; b < batch; ++b)
