@@ -174,7 +174,13 @@ def copy_ceiling(nbytes=1 << 30, reps=8):
             "kind": "device-to-device copy of one buffer, read + written bytes over the mean copy time"}
 
 
-def cpu_baseline(m, host_g, host_layers, prompt, D, tau, budget_s=12.0, max_steps=64, prompt_tokens=8):
+def weight_params(m):
+    """Weight elements every row of a step is multiplied with: the projections of all layers and the LM head."""
+    nq, nk = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim
+    return m.n_layers * (m.hidden * (nq + 2 * nk) + nq * m.hidden + 3 * m.hidden * m.ffn) + m.vocab * m.hidden
+
+
+def cpu_baseline(m, host_g, host_layers, prompt, D, tau, budget_s=12.0, max_steps=64, prompt_tokens=8, ctx_tokens=0.0):
     """The oracle as it stands, timed on a bounded sample: decode steps of one sequence until about budget_s seconds."""
     from oracle import oracle as orc
     om = orc.model_from_inputs(m, host_g, host_layers)
@@ -193,7 +199,13 @@ def cpu_baseline(m, host_g, host_layers, prompt, D, tau, budget_s=12.0, max_step
     return {"value": acc / t_steps, "unit": "accepted tokens/s", "cores": orc.num_threads(), "kind": "oracle",
             "sample": f"sequence 0 truncated to its first {prompt_tokens} prompt tokens, {n_steps} decode steps, all "
                       f"{m.n_layers} layers and the full vocabulary; the oracle decodes one sequence at a time, so its rate "
-                      f"does not grow with the batch (prefill of the sample took {t_pre:.1f} s, not counted)",
+                      f"does not grow with the batch (prefill of the sample took {t_pre:.1f} s, not counted). The short "
+                      f"context is the bound on the sample, not a shortcut that matters: an oracle step is {D + 1} rows through "
+                      f"every weight matrix ({2 * (D + 1) * weight_params(m) / 1e9:.0f} GFLOP) plus attention over the context "
+                      f"({4 * (D + 1) * m.n_layers * m.n_q_heads * m.head_dim * ctx_tokens / 1e9:.1f} GFLOP at the workload's mean "
+                      f"context of {ctx_tokens:.0f} tokens), so by operation count its step at that context would be about "
+                      f"{100 * 2 * m.n_layers * m.n_q_heads * m.head_dim * ctx_tokens / weight_params(m):.0f} % slower (an extrapolation, "
+                      f"not a measurement)",
             "ms_per_step_per_sequence": 1e3 * t_steps / n_steps}
 
 
@@ -367,7 +379,8 @@ def main():
     del ctx
     torch.cuda.empty_cache()
     if want_cpu:
-        out["cpu_baseline"] = cpu_baseline(m, host_g, host_layers, prompts[0], D, tau, prompt_tokens=min(8, len(prompts[0])))
+        out["cpu_baseline"] = cpu_baseline(m, host_g, host_layers, prompts[0], D, tau, prompt_tokens=min(8, len(prompts[0])),
+                                           ctx_tokens=main_r["ctx_mean"])
     else:
         out["cpu_baseline"] = None
     print(json.dumps(out))
