@@ -190,34 +190,48 @@ __global__ __launch_bounds__(256, (MT == 4 ? 2 : 1)) void gemm_mfma_k(MfmaArgs a
         __syncthreads();                                                                                          \
     }
 /* ---- two weight sets (128-row tiles): a single activation operand set bq_; each fragment is re-read in place
-   right after the MFMAs that used it (slot = the MFMAs of one 32-row sub-tile at one k-step).  The slice's global
-   loads are dealt out one per slot so that the load unit never holds the wavefront up: activations first, then
-   weights in the order the next slice consumes them.  (Publishing the next activations before the last k-step, to
-   cover the barrier with MFMAs, was measured and is slower: it shortens the time the activation loads have to land.) */
-#define SDLM_SLOT(WC, ks, mt, reload)                                                                             \
+   right after the MFMAs that used it (slot = the MFMAs of one 32-row sub-tile at one k-step).  The slice is pipelined
+   across its own boundary so that the MFMA stream never waits for LDS:
+     k-steps 0, 1   MFMAs; the weight loads of the next slice dealt out over the slots (the load unit never holds the
+                    wavefront up)
+     publish        the activations of the next slice (requested a whole slice ago) go registers -> the other LDS buffer
+     k-step 2       MFMAs; the activation loads of the slice after next, one per slot
+     barrier        the other buffer is complete; nobody reads this slice's buffer after k-step 2 (the fragments of
+                    k-step 3 are already in registers)
+     k-step 3       MFMAs; each fragment register is refilled with the next slice's first fragment from the other buffer
+   The next slice therefore starts with its operands in registers, and the LDS writes complete under k-step 2. */
+#define SDLM_SLOT(WC, ks, mt, SRC, koff, vm)                                                                      \
     if constexpr ((mt) < MTA_) {                                                                                  \
         _Pragma("unroll") for (int nt = 0; nt < NT; ++nt)                                                        \
             acc[nt][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(WC[nt][ks], bq_[mt], acc[nt][mt], 0, 0, 0);     \
-        if (reload) bq_[mt] = *(const bf16x8 *)&Xs[buf][(mt) * 32 + brow][((ks) + 1) * 16 + bk];                  \
-        __builtin_amdgcn_sched_group_barrier(0x020, ((ks) * MTA_ + (mt) < MTA_ + 4 * NT) ? 1 : 0, 0);             \
+        bq_[mt] = *(const bf16x8 *)&Xs[SRC][(mt) * 32 + brow][(koff) + bk];                                       \
+        __builtin_amdgcn_sched_group_barrier(0x020, (vm), 0);                                                     \
         __builtin_amdgcn_sched_group_barrier(0x008, NT, 0);                                                       \
-        __builtin_amdgcn_sched_group_barrier(0x100, (reload) ? 1 : 0, 0);                                         \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                                                        \
     }
-#define SDLM_KSTEP2(WC, ks, reload)                                                                               \
-    SDLM_SLOT(WC, ks, 0, reload) SDLM_SLOT(WC, ks, 1, reload) SDLM_SLOT(WC, ks, 2, reload) SDLM_SLOT(WC, ks, 3, reload) \
-    SDLM_SLOT(WC, ks, 4, reload) SDLM_SLOT(WC, ks, 5, reload)
+/* weight loads of slot i of the 2 MTA_ slots of k-steps 0 and 1: 4 NT loads spread evenly */
+#define SDLM_WVM(i) (((i) + 1) * 4 * NT / (2 * MTA_) - (i) * 4 * NT / (2 * MTA_))
+#define SDLM_KSTEP2(WC, ks, SRC, koff, VM)                                                                        \
+    SDLM_SLOT(WC, ks, 0, SRC, koff, VM(0)) SDLM_SLOT(WC, ks, 1, SRC, koff, VM(1)) SDLM_SLOT(WC, ks, 2, SRC, koff, VM(2)) \
+    SDLM_SLOT(WC, ks, 3, SRC, koff, VM(3)) SDLM_SLOT(WC, ks, 4, SRC, koff, VM(4)) SDLM_SLOT(WC, ks, 5, SRC, koff, VM(5))
+#define SDLM_VM_W0(mt) SDLM_WVM(mt)
+#define SDLM_VM_W1(mt) SDLM_WVM(MTA_ + (mt))
+#define SDLM_VM_ONE(mt) 1
+#define SDLM_VM_NONE(mt) 0
 #define SDLM_STAGE2(WC, WN, stage)                                                                                \
     {                                                                                                             \
-        SDLM_LOAD_X((stage) + 1);                                                                                 \
         SDLM_LOAD_W(WN, (stage) + 1);                                                                             \
-        bf16x8 bq_[MT];                                                                                           \
-        _Pragma("unroll") for (int mt = 0; mt < MTA_; ++mt) bq_[mt] = *(const bf16x8 *)&Xs[buf][mt * 32 + brow][bk]; \
-        __builtin_amdgcn_sched_group_barrier(0x100, MTA_, 0);                                                     \
-        SDLM_KSTEP2(WC, 0, 1) SDLM_KSTEP2(WC, 1, 1) SDLM_KSTEP2(WC, 2, 1) SDLM_KSTEP2(WC, 3, 0)                   \
+        SDLM_KSTEP2(WC, 0, buf, 16, SDLM_VM_W0) SDLM_KSTEP2(WC, 1, buf, 32, SDLM_VM_W1)                           \
         __builtin_amdgcn_sched_barrier(0);                                                                        \
         _Pragma("unroll") for (int i = 0; i < MTA_; ++i) *(u32x4 *)&Xs[buf ^ 1][i * 32 + xrow][xchunk * 8] = xr[i]; \
-        buf ^= 1;                                                                                                 \
+        __builtin_amdgcn_sched_barrier(0);                                                                        \
+        SDLM_LOAD_X((stage) + 2);                                                                                 \
+        SDLM_KSTEP2(WC, 2, buf, 48, SDLM_VM_ONE)                                                                  \
+        __builtin_amdgcn_sched_barrier(0);                                                                        \
         __syncthreads();                                                                                          \
+        SDLM_KSTEP2(WC, 3, buf ^ 1, 0, SDLM_VM_NONE)                                                              \
+        __builtin_amdgcn_sched_barrier(0);                                                                        \
+        buf ^= 1;                                                                                                 \
     }
 /* The whole k loop for a row block of which only the first MTA_VALUE 32-row sub-tiles hold rows (the last block of
    a launch is usually ragged): the empty sub-tiles' loads, LDS traffic and MFMAs are not issued at all.  Full
@@ -232,6 +246,11 @@ __global__ __launch_bounds__(256, (MT == 4 ? 2 : 1)) void gemm_mfma_k(MfmaArgs a
         if (WSETS == 3) SDLM_LOAD_W(w1, s_begin + 1);                                                             \
         _Pragma("unroll") for (int i = 0; i < MTA_; ++i) *(u32x4 *)&Xs[0][i * 32 + xrow][xchunk * 8] = xr[i];    \
         __syncthreads();                                                                                          \
+        bf16x8 bq_[MT];                                                                                           \
+        if constexpr (WSETS == 2) {   /* the pipelined slice expects its first fragments and the next activations */ \
+            SDLM_LOAD_X(s_begin + 1);                                                                             \
+            _Pragma("unroll") for (int mt = 0; mt < MTA_; ++mt) bq_[mt] = *(const bf16x8 *)&Xs[0][mt * 32 + brow][bk]; \
+        }                                                                                                         \
         int s = s_begin;                                                                                          \
         if constexpr (WSETS == 3) {                                                                               \
             for (; s + 3 <= s_end; s += 3) {                                                                      \
@@ -268,6 +287,11 @@ __global__ __launch_bounds__(256, (MT == 4 ? 2 : 1)) void gemm_mfma_k(MfmaArgs a
 #undef SDLM_KSTEP
 #undef SDLM_KSTEP2
 #undef SDLM_SLOT
+#undef SDLM_WVM
+#undef SDLM_VM_W0
+#undef SDLM_VM_W1
+#undef SDLM_VM_ONE
+#undef SDLM_VM_NONE
 #undef SDLM_LOAD_W
 #undef SDLM_LOAD_X
 
