@@ -549,6 +549,136 @@ __global__ __launch_bounds__(SK_W * 64) void swiglu_skinny_k(MfmaArgs a)
     else *(uint32_t *)dst = pack_bf16(o[0], o[EL - 1]);
 }
 
+// ------------------------------------------------------------------------------------------------ QKV + RoPE + K/V placement for <= 32 rows
+// For steps of at most 32 rows (a single sequence, or a few with small blocks) the QKV projection, the rotation and the
+// K/V placement are one kernel: such steps are bound by their kernel boundaries, and here the projection needs no split
+// along k between workgroups, so its epilogue sees complete sums.  Same scheme as the gate/up kernel above: a workgroup
+// owns two 32-feature tiles, here features [32 t, 32 t + 32) and the same range 64 further on of one head, i.e. both
+// members of every rotate-half pair (i, i + d/2); its four wavefronts each take a quarter of k and the quarters are added
+// in wavefront order through LDS.  The epilogue is the RoPE + K/V placement kernel's: queries and keys rotated at the
+// row's position, a pending row's K/V to the cache slot of its position, any other row's to slot `kind` of its staging tile.
+struct QkvSkinnyArgs {
+    const bf16_t *X, *Wp, *bias;
+    const int32_t *pR;
+    int max_rows, K, Hq;
+    bf16_t *q_out, *pool;
+    KvGeom kg;
+    RowMeta rm;
+    SeqState st;
+    const float2 *rope;
+};
+
+constexpr int QK_U = 12;   // k steps per register set: two sets cover a quarter of k = 1536 at once (one memory round trip)
+
+__global__ __launch_bounds__(SK_W * 64) void qkv_rope_skinny_k(QkvSkinnyArgs a)
+{
+    __shared__ float part[SK_W][2][16][64];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int head = blockIdx.x >> 1, hh = blockIdx.x & 1;   // heads: Hq of q, then Hkv of k, then Hkv of v; hh: which 32 of the first 64 features
+    const int KS = a.K >> 4, per = (KS + SK_W - 1) / SK_W;
+    const int k_begin = wave * per, k_end = min(KS, k_begin + per);
+    const bf16_t *wa = a.Wp + ((size_t)(head * 4 + hh) * KS) * 512 + lane * 8, *wb = wa + (size_t)2 * KS * 512;
+    bf16x8 g0[QK_U], u0[QK_U], x0[QK_U], g1[QK_U], u1[QK_U], x1[QK_U];
+#define SDLM_SK_LOAD_W(G, U, kb) \
+    _Pragma("unroll") for (int u = 0; u < QK_U; ++u) { \
+        const size_t o = (size_t)min((kb) + u, KS - 1) * 512; \
+        G[u] = *(const bf16x8 *)(wa + o); U[u] = *(const bf16x8 *)(wb + o); }
+#define SDLM_SK_LOAD_X(X, kb) \
+    _Pragma("unroll") for (int u = 0; u < QK_U; ++u) X[u] = *(const bf16x8 *)(xp + min((kb) + u, KS - 1) * 16);
+#define SDLM_SK_MMA(G, U, X, kb) \
+    _Pragma("unroll") for (int u = 0; u < QK_U; ++u) if ((kb) + u < k_end) { \
+        aa = __builtin_amdgcn_mfma_f32_32x32x16_bf16(G[u], X[u], aa, 0, 0, 0); \
+        ab = __builtin_amdgcn_mfma_f32_32x32x16_bf16(U[u], X[u], ab, 0, 0, 0); }
+    SDLM_SK_LOAD_W(g0, u0, k_begin)   // the weights do not wait for the row count
+    if (k_begin + QK_U < k_end) { SDLM_SK_LOAD_W(g1, u1, k_begin + QK_U) }
+    const int R = min(*a.pR, a.max_rows);
+    if (R <= 0) return;
+    const int row = lane & 31, rr = min(row, R - 1);
+    const int pos = a.rm.pos[rr], kind = a.rm.kind[rr], b = a.rm.seq[rr], stg = a.rm.stg[rr];   // requested with the operands
+    const bf16_t *xp = a.X + (size_t)rr * a.K + (lane >> 5) * 8;
+    SDLM_SK_LOAD_X(x0, k_begin)
+    if (k_begin + QK_U < k_end) { SDLM_SK_LOAD_X(x1, k_begin + QK_U) }
+    // what the epilogue needs beside the sums is requested now as well: rotation factors, bias, the page of a cached position
+    const int d = a.kg.head_dim, half = d >> 1, Hk = a.kg.n_kv_heads;
+    const int i0 = hh * 32 + wave * 8 + (lane >> 5) * 4;   // this lane's four features: index within the first half of the head
+    const bool is_q = head < a.Hq, is_v = head >= a.Hq + Hk;
+    float2 t[4];
+    float blo[4] = {0.f, 0.f, 0.f, 0.f}, bhi[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        t[e] = is_v ? make_float2(1.f, 0.f) : a.rope[(size_t)pos * half + i0 + e];
+        if (a.bias) { blo[e] = bf16_to_f(a.bias[head * d + i0 + e]); bhi[e] = bf16_to_f(a.bias[head * d + half + i0 + e]); }
+    }
+    int page = stg, slot = kind;
+    if (!is_q && kind < 0) { page = a.st.page_table[(size_t)b * a.kg.pages_per_seq + pos / PAGE]; slot = pos % PAGE; }
+    f32x16 aa, ab;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { aa[v] = 0.f; ab[v] = 0.f; }
+    for (int k0 = k_begin; k0 < k_end; k0 += 2 * QK_U) {
+        SDLM_SK_MMA(g0, u0, x0, k0)
+        if (k0 + 2 * QK_U < k_end) { SDLM_SK_LOAD_W(g0, u0, k0 + 2 * QK_U) SDLM_SK_LOAD_X(x0, k0 + 2 * QK_U) }
+        SDLM_SK_MMA(g1, u1, x1, k0 + QK_U)
+        if (k0 + 3 * QK_U < k_end) { SDLM_SK_LOAD_W(g1, u1, k0 + 3 * QK_U) SDLM_SK_LOAD_X(x1, k0 + 3 * QK_U) }
+    }
+#undef SDLM_SK_LOAD_W
+#undef SDLM_SK_LOAD_X
+#undef SDLM_SK_MMA
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { part[wave][0][v][lane] = aa[v]; part[wave][1][v][lane] = ab[v]; }
+    __syncthreads();
+    // accumulator element v of lane l: feature 8*(v/4) + 4*(l/32) + v%4 of the tile, activation row l%32; wavefront w
+    // finishes elements 4w .. 4w+3 of every lane: four consecutive features of one row, and their partners 64 further on
+    static_assert(SK_W == 4, "one wavefront finishes four consecutive features");
+    if (row >= R) return;
+    float lo[4], hi[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        float sa = part[0][0][wave * 4 + e][lane], sb = part[0][1][wave * 4 + e][lane];
+#pragma unroll
+        for (int w = 1; w < SK_W; ++w) { sa += part[w][0][wave * 4 + e][lane]; sb += part[w][1][wave * 4 + e][lane]; }
+        sa += blo[e]; sb += bhi[e];
+        lo[e] = is_v ? sa : sa * t[e].x - sb * t[e].y;
+        hi[e] = is_v ? sb : sb * t[e].x + sa * t[e].y;
+    }
+    if (is_q) {
+        bf16_t *q = a.q_out + ((size_t)row * a.Hq + head) * d + i0;
+        *(uint2 *)q = make_uint2(pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]));
+        *(uint2 *)(q + half) = make_uint2(pack_bf16(hi[0], hi[1]), pack_bf16(hi[2], hi[3]));
+        return;
+    }
+    if (page < 0) return;   // unbacked position: only reachable after a reported pool exhaustion
+    const int hk = is_v ? head - a.Hq - Hk : head - a.Hq;
+    bf16_t *tile = a.pool + a.kg.tile(page, hk);
+    if (!is_v) {
+        // k_off(slot, i) keeps eight consecutive features of a slot together: i0 is a multiple of four
+        *(uint2 *)(tile + k_off(slot, i0)) = make_uint2(pack_bf16(lo[0], lo[1]), pack_bf16(lo[2], lo[3]));
+        *(uint2 *)(tile + k_off(slot, i0 + half)) = make_uint2(pack_bf16(hi[0], hi[1]), pack_bf16(hi[2], hi[3]));
+    } else {
+        bf16_t *Vb = tile + PAGE * d;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            Vb[v_off(slot, i0 + e)] = f_to_bf16(lo[e]);
+            Vb[v_off(slot, i0 + half + e)] = f_to_bf16(hi[e]);
+        }
+    }
+}
+
+bool qkv_rope_skinny_applies(const sdlm_model_cfg *m, int max_rows)
+{
+    return mfma_supported(m) && max_rows <= 32 && m->head_dim == 128;
+}
+
+void launch_qkv_rope_skinny(hipStream_t s, const sdlm_model_cfg *m, const void *X, const void *w_packed, const void *bias, const int32_t *p_rows,
+                            int max_rows, void *q_out, void *pool_layer, const KvGeom &kg, const RowMeta &rm, const SeqState &st, const float2 *rope)
+{
+    QkvSkinnyArgs a;
+    a.X = (const bf16_t *)X; a.Wp = (const bf16_t *)w_packed; a.bias = (const bf16_t *)bias; a.pR = p_rows;
+    a.max_rows = max_rows; a.K = m->hidden; a.Hq = m->n_q_heads;
+    a.q_out = (bf16_t *)q_out; a.pool = (bf16_t *)pool_layer; a.kg = kg; a.rm = rm; a.st = st; a.rope = rope;
+    hipLaunchKernelGGL(qkv_rope_skinny_k, dim3(2 * (m->n_q_heads + 2 * m->n_kv_heads)), dim3(SK_W * 64), 0, s, a);
+}
+
 // ------------------------------------------------------------------------------------------------ launch policy
 struct TileChoice { int MT, NT, splits; };
 

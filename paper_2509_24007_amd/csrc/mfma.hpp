@@ -36,6 +36,11 @@ int launch_gemm_mfma(hipStream_t s, int epi, const GemmArgs &a, float *slabs, si
 bool launch_attn_mfma(hipStream_t s, const sdlm_model_cfg *m, int max_seq_len, const void *q, void *out, const void *pool_layer,
                       const KvGeom &kg, const RowMeta &rm, const SeqState &st, int D, int max_groups, void *scratch, size_t scratch_bytes,
                       int part, bool two_staging);
+// Steps of at most 32 rows: QKV projection, rotation and K/V placement in one launch (same results as the projection
+// followed by the RoPE + K/V placement kernel, up to the order in which the k partial sums are added).
+bool qkv_rope_skinny_applies(const sdlm_model_cfg *m, int max_rows);
+void launch_qkv_rope_skinny(hipStream_t s, const sdlm_model_cfg *m, const void *X, const void *w_packed, const void *bias, const int32_t *p_rows,
+                            int max_rows, void *q_out, void *pool_layer, const KvGeom &kg, const RowMeta &rm, const SeqState &st, const float2 *rope);
 void launch_lmhead_mfma(hipStream_t s, const void *xhat, const void *w_packed, const int32_t *p_rows, int max_rows, int min_rows, int V, int h,
                         float scale, int conf_fn, float *logits_out, void *scratch, int32_t *ids, float *conf);
 

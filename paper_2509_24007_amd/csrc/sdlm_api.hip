@@ -276,15 +276,20 @@ void run_layers(sdlm_ctx *c, int rows, int groups, int rows_sure, bool cache_onl
         char *pool_l = c->pool + (size_t)l * c->kg.layer_stride * e;
         run_taps(c, l, 0, c->x, (size_t)rows * h * 4);
         { Phase p(c, SDLM_PH_NORM); launch_rmsnorm(s, dt, c->xn, c->x, w.attn_norm, h, m.rms_eps, nullptr, c->rm.counts, rows, rows_sure, c->slabs, c->pend_slabs, c->pend_stride); c->pend_slabs = 0; }
-        int qkv_slabs = 1;
-        {
-            Phase p(c, SDLM_PH_QKV);
-            GemmArgs a{c->xn, w.wqkv, nullptr, m.has_qkv_bias ? w.bqkv : nullptr, c->qkv, nullptr, c->rm.counts, rows, nqkv, h, 1.f, rows_sure};
-            if (c->L.mfma) qkv_slabs = launch_gemm_mfma(s, EPI_STORE_F32, a, c->slabs, c->L.slab_floats, false); else launch_gemm_generic(s, dt, EPI_STORE_F32, a);
-        }
-        {
-            Phase p(c, SDLM_PH_ROPE);
-            launch_rope_scatter(s, dt, qkv_slabs > 1 ? c->slabs : c->qkv, qkv_slabs, (size_t)rows * nqkv, c->q, pool_l, c->kg, c->rm, c->st, c->rope, m.n_q_heads, rows, rows_sure);
+        if (c->L.mfma && qkv_rope_skinny_applies(&m, rows)) {
+            Phase p(c, SDLM_PH_QKV);   // projection, rotation and K/V placement in one launch
+            launch_qkv_rope_skinny(s, &m, c->xn, w.wqkv, m.has_qkv_bias ? w.bqkv : nullptr, c->rm.counts, rows, c->q, pool_l, c->kg, c->rm, c->st, c->rope);
+        } else {
+            int qkv_slabs = 1;
+            {
+                Phase p(c, SDLM_PH_QKV);
+                GemmArgs a{c->xn, w.wqkv, nullptr, m.has_qkv_bias ? w.bqkv : nullptr, c->qkv, nullptr, c->rm.counts, rows, nqkv, h, 1.f, rows_sure};
+                if (c->L.mfma) qkv_slabs = launch_gemm_mfma(s, EPI_STORE_F32, a, c->slabs, c->L.slab_floats, false); else launch_gemm_generic(s, dt, EPI_STORE_F32, a);
+            }
+            {
+                Phase p(c, SDLM_PH_ROPE);
+                launch_rope_scatter(s, dt, qkv_slabs > 1 ? c->slabs : c->qkv, qkv_slabs, (size_t)rows * nqkv, c->q, pool_l, c->kg, c->rm, c->st, c->rope, m.n_q_heads, rows, rows_sure);
+            }
         }
         run_taps(c, l, 5, c->q, (size_t)rows * nq * e);
         if (cache_only && l == m.n_layers - 1 && c->taps.empty()) break;   // nothing downstream of the last layer's K/V is used
