@@ -739,8 +739,8 @@ static TileChoice choose(int epi, int rows, int min_rows, int N, int K, size_t s
     }
     // A launch that would put two 128 x 256 workgroups on every compute unit runs as 128 x 512 workgroups of eight wavefronts
     // (measured on the 7B gate/up shape: 2.5 % faster; with fewer workgroups than units the wider tile only idles units)
-    if (epi == EPI_SWIGLU && c.MT == 4 && c.NT == 2) {   // (the LM head was measured too: slower with one row block, equal with two)
-        const long blocks4 = (N + 127) / 128;
+    if (epi != EPI_LMHEAD && c.MT == 4 && c.NT == 2 && c.splits == 1) {   // (the LM head was measured too: slower with one row block, equal with two)
+        const long blocks4 = epi == EPI_SWIGLU ? (N + 127) / 128 : (N + 255) / 256;
         if (blocks4 * sure_blocks(rows, min_rows, c.MT) > 256) c.WV = 8;
     }
     return c;
@@ -761,7 +761,7 @@ static void launch_cfg(hipStream_t s, const TileChoice &c, MfmaArgs &a, int min_
 #define SDLM_GO(MT_, NT_) hipLaunchKernelGGL((gemm_mfma_k<MT_, NT_, EPI>), grid, block, 0, s, a)
     if (EPI == EPI_SWIGLU || EPI == EPI_LMHEAD || c.NT == 2) {
         if (c.MT == 1) SDLM_GO(1, 2); else if (c.MT == 2) SDLM_GO(2, 2); else if (c.MT == 6 && EPI == EPI_SWIGLU) hipLaunchKernelGGL((gemm_mfma_k<(EPI == EPI_SWIGLU ? 6 : 4), 2, EPI>), grid, block, 0, s, a);
-        else if (c.WV == 8) hipLaunchKernelGGL((gemm_mfma_k<4, 2, (EPI == EPI_SWIGLU || EPI == EPI_LMHEAD) ? EPI : EPI_SWIGLU, 8>), grid, block, 0, s, a);
+        else if (c.WV == 8) hipLaunchKernelGGL((gemm_mfma_k<4, 2, EPI, 8>), grid, block, 0, s, a);
         else SDLM_GO(4, 2);
     } else {
         if (EPI == EPI_STORE_F32 || EPI == EPI_RESID) {
