@@ -739,7 +739,7 @@ static TileChoice choose(int epi, int rows, int min_rows, int N, int K, size_t s
     }
     // A launch that would put two 128 x 256 workgroups on every compute unit runs as 128 x 512 workgroups of eight wavefronts
     // (measured on the 7B gate/up shape: 2.5 % faster; with fewer workgroups than units the wider tile only idles units)
-    if (epi != EPI_LMHEAD && c.MT == 4 && c.NT == 2 && c.splits == 1) {   // (the LM head was measured too: slower with one row block, equal with two)
+    if ((epi == EPI_SWIGLU || epi == EPI_RESID) && c.MT == 4 && c.NT == 2 && c.splits == 1) {   // (measured and not faster: the LM head, the prefill QKV projection)
         const long blocks4 = epi == EPI_SWIGLU ? (N + 127) / 128 : (N + 255) / 256;
         if (blocks4 * sure_blocks(rows, min_rows, c.MT) > 256) c.WV = 8;
     }
