@@ -234,8 +234,8 @@ int sdlm_debug_read_kv(sdlm_ctx *ctx, int32_t layer, int32_t seq, int32_t kv_hea
 /*
  * Host logic only (no GPU work): the launch shape the bf16 matrix-core GEMM takes for `rows` launch rows of which
  * `min_rows` certainly exist (0: unknown), an [n, k] weight matrix (k a multiple of 64) and an epilogue (0: plain fp32
- * store, 1: residual add, 2: SiLU(gate)*up, 3: LM head).  Outputs: rows and columns of a workgroup's tile and the
- * number of splits along k.  For tests of the tile policy.  Errors: SDLM_EINVAL.
+ * store, 1: residual add, 2: SiLU(gate)*up, 3: LM head).  Outputs: rows and columns of a workgroup's tile (512 columns:
+ * a workgroup of eight wavefronts, else four) and the number of splits along k.  For tests of the tile policy.  Errors: SDLM_EINVAL.
  */
 int sdlm_debug_gemm_plan(int32_t epilogue, int32_t rows, int32_t min_rows, int32_t n, int32_t k, int32_t *tile_rows, int32_t *tile_cols,
                          int32_t *splits);

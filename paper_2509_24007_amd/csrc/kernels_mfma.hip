@@ -773,10 +773,10 @@ static void launch_cfg(hipStream_t s, const TileChoice &c, MfmaArgs &a, int min_
 #undef SDLM_GO
 }
 
-void mfma_gemm_plan(int epi, int rows, int min_rows, int N, int K, size_t slab_room_floats, int *MT, int *NT, int *splits)
+void mfma_gemm_plan(int epi, int rows, int min_rows, int N, int K, size_t slab_room_floats, int *MT, int *NT, int *splits, int *wavefronts)
 {
     TileChoice c = choose(epi, rows, min_rows, N, K, slab_room_floats);
-    *MT = c.MT; *NT = c.NT; *splits = c.splits;
+    *MT = c.MT; *NT = c.NT; *splits = c.splits; *wavefronts = c.WV;
 }
 
 int launch_gemm_mfma(hipStream_t s, int epi, const GemmArgs &g, float *slabs, size_t slab_room_floats, bool defer_reduce)

@@ -23,9 +23,9 @@ int mfma_group_rows(const sdlm_model_cfg *m);
 // dst_rows rows.  interleave: 0 plain; 1 / 2: the matrix is the gate / up half of the fused gate-up matrix,
 // whose 32-row tiles alternate gate, up.
 void launch_pack_mfma(hipStream_t s, void *dst, const void *src, int N, int K, int dst_row0, int dst_rows, int interleave);
-// The launch shape launch_gemm_mfma would take (host logic only): row-tile height in 32-row units, column-tile width in
-// 128-column units, number of k splits.
-void mfma_gemm_plan(int epi, int rows, int min_rows, int N, int K, size_t slab_room_floats, int *MT, int *NT, int *splits);
+// The launch shape launch_gemm_mfma would take (host logic only): row-tile height in 32-row units, 32-column bands per
+// wavefront, number of k splits, wavefronts per workgroup (a workgroup's tile is 32 MT rows x 32 NT wavefronts columns).
+void mfma_gemm_plan(int epi, int rows, int min_rows, int N, int K, size_t slab_room_floats, int *MT, int *NT, int *splits, int *wavefronts);
 // Returns the number of split-k slabs written to `slabs` (1: the result is complete in a.Yf / a.Yt).  For
 // EPI_STORE_F32 the consumer always adds the slabs; for EPI_RESID the slabs are added to a.Yf here unless
 // defer_reduce, in which case the next RMSNorm adds them (slab stride = a.max_rows * a.N floats).

@@ -825,9 +825,9 @@ int sdlm_debug_gemm_plan(int32_t epilogue, int32_t rows, int32_t min_rows, int32
                          int32_t *splits)
 {
     if (!tile_rows || !tile_cols || !splits || rows < 1 || n < 1 || k < 64 || k % 64 || epilogue < 0 || epilogue > 3) return SDLM_EINVAL;
-    int mt, nt, sp;
-    mfma_gemm_plan(epilogue == 3 ? 4 : epilogue, rows, min_rows, n, k, (size_t)16 << 20, &mt, &nt, &sp);
-    *tile_rows = 32 * mt; *tile_cols = 128 * nt; *splits = sp;
+    int mt, nt, sp, wv;
+    mfma_gemm_plan(epilogue == 3 ? 4 : epilogue, rows, min_rows, n, k, (size_t)16 << 20, &mt, &nt, &sp, &wv);
+    *tile_rows = 32 * mt; *tile_cols = 32 * nt * wv; *splits = sp;
     return SDLM_OK;
 }
 

@@ -29,9 +29,16 @@ def test_policy_invariants(epi):
         for min_rows in {0, rows, max(1, rows // 2), max(1, (rows * 5) // 8)}:
             tr, tc, sp = sdlm.gemm_plan(epi, rows, min_rows, n, k)
             seen.add((tr, tc))
-            assert tr in (32, 64, 128, 192) and tc in (128, 256), (rows, n, k, tr, tc)
+            assert tr in (32, 64, 128, 192) and tc in (128, 256, 512), (rows, n, k, tr, tc)
             assert tr != 192 or (epi == SWIGLU and tc == 256)                 # the 192-row tile exists for gate/up only
-            assert tc == 256 or epi in (STORE, RESID)                          # the narrow tile has only the plain epilogues
+            assert tc >= 256 or epi in (STORE, RESID)                          # the narrow tile has only the plain epilogues
+            if tc == 512:
+                # the eight-wavefront tile: 128 rows, never split, only where the four-wavefront launch would have put more
+                # workgroups on the chip than it has compute units; not compiled for the plain-store and LM-head epilogues
+                assert tr == 128 and sp == 1 and epi in (RESID, SWIGLU)
+                col_blocks4 = -(-n // 128) if epi == SWIGLU else -(-n // 256)
+                sure_row_blocks = max(1, min(-(-rows // 128), -(-min_rows // 128))) if min_rows > 0 else -(-rows // 128)
+                assert col_blocks4 * sure_row_blocks > 256, (rows, min_rows, n, k)
             if rows <= 32:
                 assert tr == 32
             assert sp >= 1
@@ -54,10 +61,14 @@ def test_policy_on_the_benchmark_shapes():
     assert sp <= 3
     tr, tc, sp = sdlm.gemm_plan(STORE, 512, 320, 4608, 3584)
     assert sp <= 3
-    assert sdlm.gemm_plan(SWIGLU, 512, 320, 18944, 3584) == (128, 256, 1)
+    assert sdlm.gemm_plan(SWIGLU, 512, 320, 18944, 3584) == (128, 512, 1)             # 444 workgroups of four wavefronts: eight instead
     assert sdlm.gemm_plan(SWIGLU, 256, 160, 27648, 5120) == (192, 256, 1)
     assert sdlm.gemm_plan(SWIGLU, 256, 144, 11008, 2048)[0] == 128               # too few column blocks for the tall tile
     assert sdlm.gemm_plan(LMHEAD, 256, 256, 151936, 3584) == (128, 256, 1)
+    # a 4096-row prefill pass of the 7B shape: unsplit everywhere; the residual projections and gate/up take the wide tile
+    assert sdlm.gemm_plan(RESID, 4096, 4096, 3584, 18944) == (128, 512, 1)
+    assert sdlm.gemm_plan(SWIGLU, 4096, 4096, 18944, 3584) == (128, 512, 1)
+    assert sdlm.gemm_plan(STORE, 4096, 4096, 4608, 3584) == (128, 256, 1)
 
 
 def test_plan_rejects_bad_arguments():
