@@ -379,6 +379,42 @@ def test_long_prefill_cache_matches_oracle_cache_bf16(paged, prefill_rows):
     ctx.close()
 
 
+@pytest.mark.parametrize("name,lens", [
+    ("small-step", [9, 33]),                                   # at most 32 rows per step: QKV, RoPE and K/V placement are one launch
+    ("larger-step", [3 + 5 * i for i in range(9)]),            # 72 rows: projection, then the RoPE + K/V placement kernel
+])
+def test_decode_cache_matches_oracle_cache_bf16(name, lens):
+    """K/V written by decode steps on the matrix-core path: after several steps with forced acceptance counts, every cached K
+    and V vector (prompt positions and the positions of the committed tokens, whose K/V came from the pending rows of
+    later steps) against the oracle's clean cache (Sec. 3.3: only real tokens under causal attention are ever cached).
+    Both QKV paths are covered: the fused launch of small steps and the separate kernels of larger ones."""
+    m = mfma_cfg(n_q_heads=6, n_kv_heads=2, hidden=256, ffn=512)
+    om, g_dev, layers_dev = both_models(m, seed=41, std=0.05)
+    D, steps = 4, 5
+    prompts = [syn.uniform_int(41, f"dc{name}{i}", n, 0, m.vocab - 1).numpy() for i, n in enumerate(lens)]
+    ovr = syn.make_overrides(17, steps, len(lens), D, m.vocab)   # forced tokens and counts on some steps: pending runs of every length
+    ctx = gpu_context(m, g_dev, layers_dev, max_batch=len(lens), max_seq_len=max(lens) + (steps + 2) * D, D=D, tau=0.5, paged=True,
+                      n_pages=sum((n + (steps + 2) * D + 15) // 16 + 1 for n in lens))
+    assert ctx.kernel_info == "mfma-bf16"
+    st, seqs = lockstep(ctx, om, prompts, D, 0.5, steps, logit_tol=2e-2, conf_tol=1e-5, overrides=ovr, bf16=True)
+    worst_k = worst_v = 0.0
+    grown = 0
+    for b, s in enumerate(seqs):
+        grown += s.c - len(prompts[b])
+        for layer in range(m.n_layers):
+            for hk in range(m.n_kv_heads):
+                k, v = ctx.read_kv(layer, b, hk, 0, s.c)
+                k, v = k.numpy().astype(np.float64), v.numpy().astype(np.float64)
+                for pos in range(s.c):
+                    ko, vo = s.read_kv(layer, pos, hk)
+                    worst_k = max(worst_k, float(np.max(np.abs(k[pos] - ko)) / np.max(np.abs(ko))))
+                    worst_v = max(worst_v, float(np.max(np.abs(v[pos] - vo)) / np.max(np.abs(vo))))
+    print(f"decode cache {name}: {grown} positions written by pending rows, worst relative K error {worst_k:.3e}, V {worst_v:.3e}")
+    assert grown >= steps * len(lens) - len(lens)   # every step but the last one's commit has left its tokens in the cache
+    assert worst_k <= 2e-2 and worst_v <= 2e-2
+    ctx.close()
+
+
 def test_verify_position_independent_model_accepts_whole_block():
     """All-zero weights: every logit row is constant, arg-max is token 0 everywhere, so every position verifies."""
     m = gpu_cfg()
